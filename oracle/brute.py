@@ -1,0 +1,51 @@
+"""Element-by-element writing of the CLIP loss in pure Python (test infrastructure).
+
+A second, independent writing of Eq. 1 and of the per-rank restriction
+(Sec. 4.1), with explicit loops and math.exp/log only, for B <= 16.  It exists
+to catch index, sign and transposition mistakes in the vectorised oracle.
+"""
+from __future__ import annotations
+
+import math
+
+
+def _dot(u, v):
+    return math.fsum(a * b for a, b in zip(u, v))
+
+
+def brute_rank(I, T, s, rank, N):
+    """Loss and gradients of rank `rank` (sum convention, factor 1/(2B))."""
+    B, d = len(I), len(I[0])
+    b = B // N
+    c = 1.0 / (2.0 * B)
+    gI = [[0.0] * d for _ in range(B)]
+    gT = [[0.0] * d for _ in range(B)]
+    loss, gs = 0.0, 0.0
+    for i in range(rank * b, (rank + 1) * b):
+        # image i looks for its text among all B texts
+        cos = [_dot(I[i], T[j]) for j in range(B)]
+        mx = max(s * v for v in cos)
+        den = math.fsum(math.exp(s * v - mx) for v in cos)
+        loss += c * (mx + math.log(den) - s * cos[i])
+        for j in range(B):
+            g = math.exp(s * cos[j] - mx) / den - (1.0 if j == i else 0.0)
+            gs += c * g * cos[j]
+            for k in range(d):
+                gI[i][k] += c * s * g * T[j][k]
+                gT[j][k] += c * s * g * I[i][k]
+        # text i looks for its image among all B images
+        cos = [_dot(T[i], I[j]) for j in range(B)]
+        mx = max(s * v for v in cos)
+        den = math.fsum(math.exp(s * v - mx) for v in cos)
+        loss += c * (mx + math.log(den) - s * cos[i])
+        for j in range(B):
+            g = math.exp(s * cos[j] - mx) / den - (1.0 if j == i else 0.0)
+            gs += c * g * cos[j]
+            for k in range(d):
+                gT[i][k] += c * s * g * I[j][k]
+                gI[j][k] += c * s * g * T[i][k]
+    return loss, gI, gT, gs
+
+
+def brute_full(I, T, s):
+    return brute_rank(I, T, s, 0, 1)

@@ -1,0 +1,13 @@
+"""Seeded synthetic inputs shared by the tests, the benchmark and the oracle checks.
+
+This package only *draws inputs*.  It holds none of the contrastive-loss
+arithmetic: no logits, no softmax, no gradients.
+"""
+from .features import (  # noqa: F401
+    CONFIGS,
+    WorkloadConfig,
+    bf16_bits_to_f32,
+    clip_pairs,
+    f32_to_bf16_bits,
+    make_config_inputs,
+)
