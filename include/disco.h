@@ -1,0 +1,114 @@
+/*
+ * disco.h - C ABI of the decomposed CLIP contrastive loss for one MI355X (gfx950).
+ *
+ * The operation is the second segment of the paper's Alg. 1 (Sec. 4.2): given the
+ * all-gathered image and text features I, T (B x d), the rank r of N and the logit
+ * multiplier s (Alg. 1's `t`), rank r forms only the two b x B logit blocks
+ *     A = s * I_r * T^T        C = s * T_r * I^T            (b = B/N, Sec. 4.1 Eq. 6)
+ * takes the row-wise softmax cross-entropy of each against the global diagonal
+ * (label of local row i is column r*b + i, Alg. 1 `labels = arange(b) + b*rank`),
+ * and back-propagates: the intra-rank gradient lands in rows R_r = [r*b, (r+1)*b)
+ * and the inter-rank gradient in ALL B rows of gI and gT (Sec. 4.1 Eq. 4, 5).  The
+ * all_reduce of Eq. 7 is replaced by adding the N simulated ranks' outputs into the
+ * same device buffers (`accumulate`).
+ *
+ * Normalisation: Alg. 1's mean over b rows, the /2 and the all_reduce(AVG) compose
+ * to the factor c = 1/(2B).  Every per-rank output carries c, so the SUM over
+ * r = 0..N-1 of (loss, gI, gT, gs) equals the loss and gradients of the original
+ * non-distributed CLIP loss (Eq. 1, Eq. 3).
+ *
+ * Pointers: every data pointer is a DEVICE pointer owned by the caller; the library
+ * allocates and frees nothing and keeps no pointer after the call returns.  All work
+ * is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream)
+ * and the call returns without synchronising.  I and T are read-only and must not
+ * overlap any output or the workspace.
+ *
+ * Errors are return codes.  On any status other than DISCO_OK and DISCO_ERR_HIP
+ * nothing was launched and no output was touched.
+ */
+#ifndef DISCO_H
+#define DISCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DISCO_API __attribute__((visibility("default")))
+
+typedef enum {
+  DISCO_OK = 0,
+  DISCO_ERR_NULL = 1,        /* a required pointer is NULL */
+  DISCO_ERR_SHAPE = 2,       /* B<=0, d<=0, N<=0, B % N != 0, rank outside [0,N), sizes beyond int32 tiles */
+  DISCO_ERR_UNSUPPORTED = 3, /* unknown dtype/path value, or the path cannot run this shape/dtype */
+  DISCO_ERR_WORKSPACE = 4,   /* workspace NULL/misaligned or smaller than disco_workspace_bytes() */
+  DISCO_ERR_HIP = 5          /* a kernel launch failed; outputs are undefined */
+} disco_status;
+
+/* dtype of I and T only.  Outputs and all accumulation are fp32. */
+typedef enum { DISCO_F32 = 0, DISCO_BF16 = 1 } disco_dtype;
+
+/*
+ * DISCO_PATH_NAIVE        fp32 FMA arithmetic on the vector ALUs, fp32 logit blocks kept in the
+ *                         workspace (2*b*B*4 bytes: the paper's 2B^2/N memory model, Sec. 4.1).
+ *                         Any B, d, N; either dtype.
+ * DISCO_PATH_MATERIALIZED bf16 MFMA tiles.  The logit blocks are computed once; the un-normalised
+ *                         softmax numerators are kept in bf16 (2*b*B*2 bytes) and feed the two
+ *                         gradient contractions.  Needs dtype bf16, d % 64 == 0, b % 256 == 0.
+ * DISCO_PATH_FUSED        bf16 MFMA tiles, streaming: row max/sum are kept on chip, logits are
+ *                         recomputed per tile in the backward pass, no b x B array exists.
+ *                         Same shape limits as MATERIALIZED.
+ * DISCO_PATH_AUTO         the fastest path that supports the arguments.
+ */
+typedef enum {
+  DISCO_PATH_AUTO = 0,
+  DISCO_PATH_NAIVE = 1,
+  DISCO_PATH_MATERIALIZED = 2,
+  DISCO_PATH_FUSED = 3
+} disco_path;
+
+/* The concrete path (1..3) that `path` resolves to for these arguments, or a negative
+ * disco_status (e.g. -DISCO_ERR_UNSUPPORTED) if the arguments are invalid for it.  Host only. */
+DISCO_API int disco_resolve_path(int64_t B, int64_t d, int32_t N, int dtype, int path);
+
+/* Bytes of device workspace the call needs (256-byte aligned pointer).  0 on invalid arguments.
+ * Host only, no HIP call. */
+DISCO_API size_t disco_workspace_bytes(int64_t B, int64_t d, int32_t N, int dtype, int path);
+
+/*
+ * One rank's forward + backward (Alg. 1 lines "scaled dot product similarities" to
+ * "loss backward"; Sec. 4.1 Eq. 4-6).
+ *
+ *   I, T        device, row-major B x d, contiguous, dtype `dtype` (bf16 = raw 16-bit patterns).
+ *               Expected L2-normalised by the caller; gradients are w.r.t. the arrays as given.
+ *   B, d        global batch and feature width.   rank, N: 0 <= rank < N, B % N == 0.
+ *   s           logit multiplier (1/temperature).
+ *   accumulate  0: loss, gI, gT, gs are overwritten (all B rows of gI and gT are defined);
+ *               1: the rank's results are added to what the buffers hold.
+ *   loss, gs    device, one fp32 each.      gI, gT: device, row-major B x d fp32.
+ *   workspace   device scratch of at least disco_workspace_bytes(...) bytes, 256-byte aligned;
+ *               contents before and after the call are unspecified.
+ */
+DISCO_API int disco_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t d, int32_t rank, int32_t N,
+                       float s, int dtype, int path, int accumulate,
+                       float* loss, float* gI, float* gT, float* gs,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The original non-distributed CLIP loss (Eq. 1, Fig. 1): the whole B x B similarity matrix on
+ * one device.  Equal in value to disco_loss_fwd_bwd(rank = 0, N = 1, accumulate = 0); the
+ * workspace size is disco_workspace_bytes(B, d, 1, dtype, path).
+ */
+DISCO_API int clip_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t d, float s, int dtype, int path,
+                      float* loss, float* gI, float* gT, float* gs,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+DISCO_API const char* disco_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DISCO_H */

@@ -1,0 +1,26 @@
+"""MI355X-native decomposed CLIP contrastive loss (DisCo): thin binding over libdisco.so.
+
+Every step of the path runs inside the HIP library; this package only marshals arguments.
+There is no CPU fallback: importing `binding` fails loudly when the library is not built.
+"""
+from .binding import (  # noqa: F401
+    DISCO_BF16,
+    DISCO_ERR_HIP,
+    DISCO_ERR_NULL,
+    DISCO_ERR_SHAPE,
+    DISCO_ERR_UNSUPPORTED,
+    DISCO_ERR_WORKSPACE,
+    DISCO_F32,
+    DISCO_OK,
+    DISCO_PATH_AUTO,
+    DISCO_PATH_FUSED,
+    DISCO_PATH_MATERIALIZED,
+    DISCO_PATH_NAIVE,
+    DiscoError,
+    clip_loss_fwd_bwd,
+    disco_loss_fwd_bwd,
+    disco_resolve_path,
+    disco_status_string,
+    disco_workspace_bytes,
+    library_path,
+)

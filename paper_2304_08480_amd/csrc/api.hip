@@ -1,0 +1,85 @@
+// Host side of libdisco: argument validation, path selection, workspace checks, dispatch.
+// No allocation, no synchronisation, no HIP call before validation has passed.
+#include "common.h"
+
+using namespace disco;
+
+namespace {
+
+int check_shape(int64_t B, int64_t d, int32_t N) {
+  if (B <= 0 || d <= 0 || N <= 0) return DISCO_ERR_SHAPE;
+  if (B % N != 0) return DISCO_ERR_SHAPE;
+  // tile indices and row offsets are kept in 32-bit registers inside the kernels
+  if (B > (int64_t)1 << 24 || d > (int64_t)1 << 16) return DISCO_ERR_SHAPE;
+  return DISCO_OK;
+}
+
+int resolve(int64_t B, int64_t d, int32_t N, int dtype, int path) {
+  int st = check_shape(B, d, N);
+  if (st != DISCO_OK) return -st;
+  if (dtype != DISCO_F32 && dtype != DISCO_BF16) return -DISCO_ERR_UNSUPPORTED;
+  switch (path) {
+    case DISCO_PATH_AUTO:
+      return mfma_supported(B, d, N, dtype) ? DISCO_PATH_MATERIALIZED : DISCO_PATH_NAIVE;
+    case DISCO_PATH_NAIVE:
+      return DISCO_PATH_NAIVE;
+    case DISCO_PATH_MATERIALIZED:
+      return mfma_supported(B, d, N, dtype) ? DISCO_PATH_MATERIALIZED : -DISCO_ERR_UNSUPPORTED;
+    case DISCO_PATH_FUSED:
+      return -DISCO_ERR_UNSUPPORTED;
+    default:
+      return -DISCO_ERR_UNSUPPORTED;
+  }
+}
+
+}  // namespace
+
+extern "C" int disco_resolve_path(int64_t B, int64_t d, int32_t N, int dtype, int path) {
+  return resolve(B, d, N, dtype, path);
+}
+
+extern "C" size_t disco_workspace_bytes(int64_t B, int64_t d, int32_t N, int dtype, int path) {
+  int r = resolve(B, d, N, dtype, path);
+  if (r == DISCO_PATH_NAIVE) return naive_workspace_bytes(B, d, N);
+  if (r == DISCO_PATH_MATERIALIZED) return mfma_stored_workspace_bytes(B, d, N);
+  return 0;
+}
+
+extern "C" int disco_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t d, int32_t rank, int32_t N,
+                                  float s, int dtype, int path, int accumulate, float* loss, float* gI, float* gT,
+                                  float* gs, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!I || !T || !loss || !gI || !gT || !gs) return DISCO_ERR_NULL;
+  int r = resolve(B, d, N, dtype, path);
+  if (r < 0) return -r;
+  if (rank < 0 || rank >= N) return DISCO_ERR_SHAPE;
+  size_t need = r == DISCO_PATH_NAIVE ? naive_workspace_bytes(B, d, N) : mfma_stored_workspace_bytes(B, d, N);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < need)
+    return DISCO_ERR_WORKSPACE;
+
+  Problem p;
+  p.I = I; p.T = T; p.B = B; p.d = d; p.rank = rank; p.N = N; p.b = B / N; p.s = s; p.dtype = dtype;
+  p.accumulate = accumulate ? 1 : 0;
+  p.loss = loss; p.gI = gI; p.gT = gT; p.gs = gs;
+  p.ws = workspace; p.ws_bytes = workspace_bytes;
+  p.stream = static_cast<hipStream_t>(hip_stream);
+  return r == DISCO_PATH_NAIVE ? naive_run(p) : mfma_stored_run(p);
+}
+
+extern "C" int clip_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t d, float s, int dtype, int path,
+                                 float* loss, float* gI, float* gT, float* gs, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+  return disco_loss_fwd_bwd(I, T, B, d, 0, 1, s, dtype, path, 0, loss, gI, gT, gs, workspace, workspace_bytes,
+                            hip_stream);
+}
+
+extern "C" const char* disco_status_string(int status) {
+  switch (status) {
+    case DISCO_OK: return "ok";
+    case DISCO_ERR_NULL: return "a required pointer is NULL";
+    case DISCO_ERR_SHAPE: return "invalid shape: need B, d, N > 0, B % N == 0, 0 <= rank < N";
+    case DISCO_ERR_UNSUPPORTED: return "dtype/path value unknown or path does not support this shape and dtype";
+    case DISCO_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or smaller than disco_workspace_bytes()";
+    case DISCO_ERR_HIP: return "a HIP kernel launch failed";
+    default: return "unknown status";
+  }
+}

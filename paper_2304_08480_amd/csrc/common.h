@@ -1,0 +1,40 @@
+// Internal declarations shared by the host dispatch and the kernel files of libdisco.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/disco.h"
+
+namespace disco {
+
+// One of the two logit blocks of a rank (Sec. 4.1 Eq. 6).  Block A: X = I_r, Y = T, query-side
+// gradient goes to gI rows R_r and key-side gradient to all rows of gT; block C is the mirror image.
+struct Problem {
+  const void* I;
+  const void* T;
+  int64_t B, d;
+  int32_t rank, N;
+  int64_t b;          // B / N
+  float s;
+  int dtype;
+  int accumulate;
+  float* loss;
+  float* gI;
+  float* gT;
+  float* gs;
+  void* ws;
+  size_t ws_bytes;
+  hipStream_t stream;
+};
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+size_t naive_workspace_bytes(int64_t B, int64_t d, int32_t N);
+int naive_run(const Problem& p);
+
+bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype);
+size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N);
+int mfma_stored_run(const Problem& p);
+
+}  // namespace disco

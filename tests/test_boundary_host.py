@@ -1,0 +1,88 @@
+"""Host-side checks of the C ABI: the library loads, exports what include/disco.h declares, and turns
+every invalid call into a status code before any GPU work (so these run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2304_08480_amd as dl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "disco.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:disco|clip)_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = ctypes.CDLL(dl.library_path())
+    names = _declared_symbols()
+    assert {"disco_loss_fwd_bwd", "clip_loss_fwd_bwd", "disco_workspace_bytes", "disco_status_string",
+            "disco_resolve_path"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    for st in range(0, 6):
+        assert dl.disco_status_string(st) not in ("", "unknown status")
+    assert dl.disco_status_string(99) == "unknown status"
+
+
+FAKE = 0x1000  # 256-aligned non-null address; never dereferenced because validation fails first
+
+
+def _call(**kw):
+    a = dict(I=FAKE, T=FAKE, B=256, d=512, rank=0, N=4, s=10.0, dtype=dl.DISCO_F32, path=dl.DISCO_PATH_NAIVE,
+             accumulate=0, loss=FAKE, gI=FAKE, gT=FAKE, gs=FAKE, workspace=FAKE, workspace_bytes=0)
+    a.update(kw)
+    return dl.disco_loss_fwd_bwd(a["I"], a["T"], a["B"], a["d"], a["rank"], a["N"], a["s"], a["dtype"], a["path"],
+                                 a["accumulate"], a["loss"], a["gI"], a["gT"], a["gs"], a["workspace"],
+                                 a["workspace_bytes"], None, check=False)
+
+
+@pytest.mark.parametrize("name", ["I", "T", "loss", "gI", "gT", "gs"])
+def test_null_pointers(name):
+    assert _call(**{name: None}) == dl.DISCO_ERR_NULL
+
+
+@pytest.mark.parametrize("kw", [dict(B=0), dict(B=-4), dict(d=0), dict(N=0), dict(B=250, N=4), dict(rank=4),
+                                dict(rank=-1), dict(B=1 << 25, N=1)])
+def test_bad_shapes(kw):
+    assert _call(**kw) == dl.DISCO_ERR_SHAPE
+
+
+@pytest.mark.parametrize("kw", [dict(dtype=7), dict(path=9), dict(path=dl.DISCO_PATH_MATERIALIZED),  # fp32 input
+                                dict(path=dl.DISCO_PATH_MATERIALIZED, dtype=dl.DISCO_BF16, d=100)])
+def test_unsupported(kw):
+    assert _call(**kw) == dl.DISCO_ERR_UNSUPPORTED
+
+
+def test_workspace_checks():
+    need = dl.disco_workspace_bytes(256, 512, 4, dl.DISCO_F32, dl.DISCO_PATH_NAIVE)
+    assert need >= 2 * 64 * 256 * 4
+    assert _call(workspace=None, workspace_bytes=need) == dl.DISCO_ERR_WORKSPACE
+    assert _call(workspace=FAKE + 8, workspace_bytes=need) == dl.DISCO_ERR_WORKSPACE
+    assert _call(workspace=FAKE, workspace_bytes=need - 1) == dl.DISCO_ERR_WORKSPACE
+
+
+def test_workspace_bytes_zero_on_bad_args():
+    assert dl.disco_workspace_bytes(250, 512, 4, dl.DISCO_F32, dl.DISCO_PATH_NAIVE) == 0
+    assert dl.disco_workspace_bytes(256, 512, 4, 5, dl.DISCO_PATH_NAIVE) == 0
+    assert dl.disco_resolve_path(250, 512, 4, dl.DISCO_F32, dl.DISCO_PATH_AUTO) == -dl.DISCO_ERR_SHAPE
+
+
+def test_naive_workspace_follows_the_papers_memory_model():
+    # Sec. 4.1: two b x B matrices instead of B x B -> 2 B^2 / N entries (fp32 here), plus O(b) row scalars
+    for B, N in ((32768, 8), (32768, 1), (196608, 64)):
+        need = dl.disco_workspace_bytes(B, 512, N, dl.DISCO_BF16, dl.DISCO_PATH_NAIVE)
+        entries = 2 * (B // N) * B
+        assert entries * 4 <= need <= entries * 4 + 64 * (B // N) + 4096
+
+
+def test_auto_falls_back_to_naive_for_fp32_and_odd_shapes():
+    assert dl.disco_resolve_path(256, 512, 4, dl.DISCO_F32, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
+    assert dl.disco_resolve_path(300, 77, 3, dl.DISCO_BF16, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
