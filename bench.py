@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the decomposed CLIP contrastive loss (fwd+bwd) on one MI355X.
+
+One step = the whole hot path for every simulated rank of the workload: for r = 0..N-1 one
+disco_loss_fwd_bwd call (two logit blocks, row softmax cross-entropy, the four gradient
+contractions, d/ds) accumulated on device into the same gI/gT/loss/gs, which stands in for
+the all_reduce of Eq. 7.  Inputs are synthetic (synth/features.py), resident in HBM before timing.
+
+Prints ONE JSON line.  `value` = pairs per second = B / t_step (equal to b / t_rank, the "samples/s
+per rank share" of the metric).  `roofline` is for the dominant kernel (the logit-tile kernel),
+timed live with HIP events recorded by the library between its stages.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3      # MI355X fp32 vector
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="b32k_n8")
+    ap.add_argument("--path", default="auto", choices=["auto", "naive", "materialized"])
+    ap.add_argument("--ranks", default="all", help="'all' (every simulated rank per step) or one rank index")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+class HipEvents:
+    """hipEvent_t handles created through the HIP runtime already loaded by torch."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so.7") if _loaded("libamdhip64.so.7") else ctypes.CDLL("libamdhip64.so")
+        self.n = n
+        self.arr = (ctypes.c_void_p * n)()
+        for i in range(n):
+            ev = ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(ev)) == 0
+            self.arr[i] = ev
+
+    def elapsed_ms(self, a, b):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), ctypes.c_void_p(self.arr[a]), ctypes.c_void_p(self.arr[b]))
+        assert rc == 0, rc
+        return ms.value
+
+
+def _loaded(name):
+    try:
+        with open("/proc/self/maps") as f:
+            return any(name in line for line in f)
+    except OSError:
+        return False
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the N ranks of the workload are simulated on it "
+              "(--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2304_08480_amd as dl
+    from synth import CONFIGS, make_config_inputs
+
+    cfg = CONFIGS[args.config]
+    B, d, N, b, s = cfg.B, cfg.d, cfg.N, cfg.b, cfg.s
+    path = {"auto": dl.DISCO_PATH_AUTO, "naive": dl.DISCO_PATH_NAIVE, "materialized": dl.DISCO_PATH_MATERIALIZED}[args.path]
+    I, T, Ib, Tb = make_config_inputs(cfg)
+    dev = torch.device("cuda:0")
+    if cfg.dtype == "bf16":
+        Id = torch.from_numpy(Ib.view(np.int16)).to(dev)
+        Td = torch.from_numpy(Tb.view(np.int16)).to(dev)
+        dt = dl.DISCO_BF16
+    else:
+        Id, Td, dt = torch.from_numpy(I).to(dev), torch.from_numpy(T).to(dev), dl.DISCO_F32
+    resolved = dl.disco_resolve_path(B, d, N, dt, path)
+    assert resolved > 0, dl.disco_status_string(-resolved)
+    ws_bytes = dl.disco_workspace_bytes(B, d, N, dt, path)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    loss = torch.zeros(1, device=dev)
+    gs = torch.zeros(1, device=dev)
+    gI = torch.zeros(B, d, device=dev)
+    gT = torch.zeros(B, d, device=dev)
+    ranks = list(range(N)) if args.ranks == "all" else [int(args.ranks)]
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for n, r in enumerate(ranks):
+            dl.disco_loss_fwd_bwd(Id, Td, B, d, r, N, s, dt, path, 1 if n > 0 else 0, loss, gI, gT, gs, ws, ws_bytes, stream)
+
+    nstages = 6 if resolved == dl.DISCO_PATH_MATERIALIZED else 5
+    ev = HipEvents(nstages + 1)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: exactly `steps` steps; stage events are recorded by the library on the same stream
+    # (the last call's events survive: one rank call of the last step)
+    dl.disco_set_stage_events(ev.arr, ev.n)
+    t_start = torch.cuda.Event(enable_timing=True)
+    t_end = torch.cuda.Event(enable_timing=True)
+    stage_ms = np.zeros(nstages)
+    stage_samples = 0
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    t_start.record(stream)
+    for k in range(args.steps):
+        step()
+    t_end.record(stream)
+    torch.cuda.synchronize()
+    wall1 = time.perf_counter()
+    total_ms = t_start.elapsed_time(t_end)
+    # the events now hold the last rank call of the last step
+    for i in range(nstages):
+        stage_ms[i] = ev.elapsed_ms(i, i + 1)
+    stage_samples = 1
+    # a few more calls only to average the stage intervals (outside the throughput figure)
+    extra = min(20, max(4, args.steps))
+    acc = np.zeros(nstages)
+    for k in range(extra):
+        dl.disco_loss_fwd_bwd(Id, Td, B, d, ranks[k % len(ranks)], N, s, dt, path, 1, loss, gI, gT, gs, ws, ws_bytes, stream)
+        torch.cuda.synchronize()
+        acc += np.array([ev.elapsed_ms(i, i + 1) for i in range(nstages)])
+    stage_avg = acc / extra
+    dl.disco_set_stage_events(None, 0)
+
+    ms_per_step = total_ms / args.steps
+    calls_per_step = len(ranks)
+    ms_per_rank = ms_per_step / calls_per_step
+    pairs_per_step = b * calls_per_step
+    value = pairs_per_step / (ms_per_step * 1e-3)
+    alg_flops_rank = 12.0 * b * B * d
+    tflops_alg = alg_flops_rank / (ms_per_rank * 1e-3) / 1e12
+
+    if resolved == dl.DISCO_PATH_MATERIALIZED:
+        names = ["prep", "logit_tiles", "merge_transpose", "key_grad_gemm", "query_split_gemm", "finalize_scalars"]
+        dom = 1
+        dom_flops = 4.0 * b * B * d                 # both blocks: 2 * (2 b B d)
+        peak, bound, unit = PEAK_BF16_TFLOPS, "mfma", "TFLOP/s"
+        dtype = "bf16"
+    else:
+        names = ["similarity", "row_softmax", "scalars", "key_grad", "query_grad"]
+        dom = int(np.argmax(stage_avg))
+        dom_flops = 4.0 * b * B * d
+        peak, bound, unit = PEAK_FP32_TFLOPS, "alu", "TFLOP/s"
+        dtype = "f32"
+    dom_ms = float(stage_avg[dom])
+    achieved = dom_flops / (dom_ms * 1e-3) / 1e12
+    roofline = {
+        "bound": bound, "kernel": names[dom], "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+        "frac": round(achieved / peak, 4), "traffic": None,
+        "avg_launch_ms": round(dom_ms, 4), "flops_per_launch": dom_flops,
+        "stages_ms": {n: round(float(v), 4) for n, v in zip(names, stage_avg)},
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import clip_oracle as oc
+        t0 = time.perf_counter()
+        ref = oc.disco_rank(I, T, s, ranks[0], N)
+        t_cpu = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        cpu = {"value": round(b / t_cpu, 2), "unit": "samples/s", "cores": cores, "kind": "oracle",
+               "sample": f"float64 oracle, one rank of the workload (rank {ranks[0]}: {b} pairs x {B} keys), {t_cpu:.2f} s",
+               "oracle_loss": ref[0]}
+
+    out = {
+        "metric": "contrastive loss fwd+bwd samples/s per rank share",
+        "value": round(value, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "B": B, "d": d, "N_simulated_ranks": N, "b": b, "s": round(s, 6),
+                   "ranks_per_step": calls_per_step, "path": {1: "naive", 2: "materialized", 3: "fused"}[resolved],
+                   "workspace_bytes": ws_bytes},
+        "ms_per_rank_call": round(ms_per_rank, 4),
+        "tflops_algorithmic": round(tflops_alg, 2),
+        "frac_of_bf16_mfma_peak_algorithmic": round(tflops_alg / PEAK_BF16_TFLOPS, 4),
+        "wall_ms_per_step": round((wall1 - wall0) * 1e3 / args.steps, 4),
+        "loss": float(loss.item()),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -105,6 +105,23 @@ DISCO_API int clip_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t
                       float* loss, float* gI, float* gT, float* gs,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Stage timing for benchmarks (measurement only; the paper reports per-operator times in Table 4).
+ * `events` is a caller-owned array of `count` hipEvent_t handles (created with timing enabled), or
+ * NULL to switch stage timing off (the default).  While set, every disco_loss_fwd_bwd /
+ * clip_loss_fwd_bwd call made from any thread records events[0] on its stream before its first
+ * kernel and events[k] after stage k, for as many stages as fit in `count`; the caller synchronises
+ * and reads the intervals with hipEventElapsedTime.  The library keeps the pointer until it is
+ * replaced.  Stages of DISCO_PATH_MATERIALIZED (DISCO_STAGES_MATERIALIZED = 6):
+ *   1 row norms + positive-pair logits   2 logit tiles + softmax numerators   3 row merge + scaled transpose
+ *   4 key-side gradient GEMM             5 query-side split GEMM              6 query finalize + scalars
+ * Stages of DISCO_PATH_NAIVE (DISCO_STAGES_NAIVE = 5): similarity, row softmax, scalars, key grad, query grad.
+ * Returns DISCO_OK, or DISCO_ERR_SHAPE if count < 0.
+ */
+#define DISCO_STAGES_MATERIALIZED 6
+#define DISCO_STAGES_NAIVE 5
+DISCO_API int disco_set_stage_events(void** events, int count);
+
 /* Static, NUL-terminated description of a status code. */
 DISCO_API const char* disco_status_string(int status);
 

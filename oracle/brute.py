@@ -49,3 +49,23 @@ def brute_rank(I, T, s, rank, N):
 
 def brute_full(I, T, s):
     return brute_rank(I, T, s, 0, 1)
+
+
+def brute_rank_term_scale(I, T, s, rank, N):
+    """Same loops as brute_rank with every gradient term replaced by its magnitude."""
+    B, d = len(I), len(I[0])
+    b = B // N
+    c = 1.0 / (2.0 * B)
+    aI = [[0.0] * d for _ in range(B)]
+    aT = [[0.0] * d for _ in range(B)]
+    for i in range(rank * b, (rank + 1) * b):
+        for (Q, K, aQ, aK) in ((I, T, aI, aT), (T, I, aT, aI)):
+            cos = [_dot(Q[i], K[j]) for j in range(B)]
+            mx = max(s * v for v in cos)
+            den = math.fsum(math.exp(s * v - mx) for v in cos)
+            for j in range(B):
+                g = abs(math.exp(s * cos[j] - mx) / den - (1.0 if j == i else 0.0))
+                for k in range(d):
+                    aQ[i][k] += c * abs(s) * g * abs(K[j][k])
+                    aK[j][k] += c * abs(s) * g * abs(Q[i][k])
+    return aI, aT

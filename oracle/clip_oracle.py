@@ -71,6 +71,48 @@ def directional_terms(X: np.ndarray, Y: np.ndarray, s: float, rows: np.ndarray):
     return ce_sum, dXq, dY, dS
 
 
+def directional_term_scale(X: np.ndarray, Y: np.ndarray, s: float, rows: np.ndarray):
+    """Sum of the magnitudes of the terms that directional_terms adds up.
+
+    aXq[i] = sum_j |P_ij - [j = i]| * |s| * |Y_j|   and   aY[j] = sum_i |P_ij - [j = i]| * |s| * |X_i|
+    (elementwise absolute values).  An implementation that rounds each factor of every product
+    to a format with unit roundoff u errs by at most about 2u times this, whatever cancels in the
+    sum itself; the parity tests use it as the scale of their elementwise bound.
+    """
+    X, Y = _f64(X), _f64(Y)
+    B, d = Y.shape
+    rows = np.asarray(rows, dtype=np.int64)
+    aXq = np.zeros((rows.size, d))
+    aY = np.zeros((B, d))
+    absY = np.abs(Y)
+    for lo in range(0, rows.size, _CHUNK):
+        idx = rows[lo:lo + _CHUNK]
+        Xc = X[idx]
+        Z = s * (Xc @ Y.T)
+        G = np.exp(Z - _row_logsumexp(Z)[:, None])
+        G[np.arange(idx.size), idx] -= 1.0
+        G = np.abs(G)
+        aXq[lo:lo + idx.size] = abs(s) * (G @ absY)
+        aY += abs(s) * (G.T @ np.abs(Xc))
+    return aXq, aY
+
+
+def disco_rank_term_scale(I, T, s: float, rank: int, N: int):
+    """Elementwise scale (B x d each) for gI_r and gT_r of disco_rank: same sums with every term's magnitude."""
+    I, T = _f64(I), _f64(T)
+    B = I.shape[0]
+    b = B // N
+    c = 1.0 / (2.0 * B)
+    R = np.arange(rank * b, (rank + 1) * b)
+    aI_q, aT_k = directional_term_scale(I, T, s, R)
+    aT_q, aI_k = directional_term_scale(T, I, s, R)
+    sI = c * aI_k
+    sI[R] += c * aI_q
+    sT = c * aT_k
+    sT[R] += c * aT_q
+    return sI, sT
+
+
 def clip_loss_full(I, T, s: float):
     """Original, non-distributed CLIP loss (Eq. 1) and its gradients.
 
@@ -137,14 +179,25 @@ def rank_row_stats(I, T, s: float, rank: int, N: int):
     return lseA, lseC
 
 
-def rank_grad_rows(I, T, s: float, rank: int, N: int, lseA, lseC, out_rows):
+def rank_loss_from_stats(I, T, s: float, rank: int, N: int, lseA, lseC) -> float:
+    """loss_r = c * sum_{i in R_r} [(lseA_i - z_ii) + (lseC_i - z_ii)],  z_ii = s <I_i, T_i>."""
+    I, T = _f64(I), _f64(T)
+    B = I.shape[0]
+    b = B // N
+    R = np.arange(rank * b, (rank + 1) * b)
+    zii = s * np.sum(I[R] * T[R], axis=1)
+    return float(np.sum((lseA - zii) + (lseC - zii)) / (2.0 * B))
+
+
+def rank_grad_rows(I, T, s: float, rank: int, N: int, lseA, lseC, out_rows, magnitudes=False):
     """Selected rows of disco_rank's gI_r and gT_r, computed one output row at a time.
 
     For an output row j, gT_r[j] = c s [ sum_{i in R_r} (P^A_ij - [j=i]) I_i ]
                                   + [j in R_r] c s sum_j' (P^C_jj' - [j'=j]) I_j'
     and gI_r[j] likewise with the roles of the blocks exchanged.  Needs the row
     log-sum-exps from rank_row_stats.  Used to spot-check outputs at sizes where
-    the dense disco_rank would take minutes.
+    the dense disco_rank would take minutes.  With magnitudes=True every term enters by its
+    absolute value, which gives the same rows of disco_rank_term_scale.
     """
     I, T = _f64(I), _f64(T)
     B, d = I.shape
@@ -155,20 +208,27 @@ def rank_grad_rows(I, T, s: float, rank: int, N: int, lseA, lseC, out_rows):
     out_rows = np.asarray(out_rows, dtype=np.int64)
     gI = np.zeros((out_rows.size, d))
     gT = np.zeros((out_rows.size, d))
+    mag = (lambda a: np.abs(a)) if magnitudes else (lambda a: a)
+    if magnitudes:
+        s_out = abs(s)
+        IR, TR, Ia, Ta = np.abs(IR), np.abs(TR), np.abs(I), np.abs(T)
+    else:
+        s_out, Ia, Ta = s, I, T
+    IRs, TRs = I[R], T[R]                                # signed copies for the logits
     for n, j in enumerate(out_rows):
-        pA = np.exp(s * (IR @ T[j]) - lseA)              # column j of P^A, length b
-        pC = np.exp(s * (TR @ I[j]) - lseC)              # column j of P^C
+        pA = np.exp(s * (IRs @ T[j]) - lseA)             # column j of P^A, length b
+        pC = np.exp(s * (TRs @ I[j]) - lseC)             # column j of P^C
         if rank * b <= j < (rank + 1) * b:
             pA[j - rank * b] -= 1.0
             pC[j - rank * b] -= 1.0
-        gT[n] = c * s * (pA @ IR)
-        gI[n] = c * s * (pC @ TR)
+        gT[n] = c * s_out * (mag(pA) @ IR)
+        gI[n] = c * s_out * (mag(pC) @ TR)
         if rank * b <= j < (rank + 1) * b:
             i = j - rank * b
             rowA = np.exp(s * (T @ I[j]) - lseA[i])      # row i of P^A over all columns
             rowA[j] -= 1.0
             rowC = np.exp(s * (I @ T[j]) - lseC[i])
             rowC[j] -= 1.0
-            gI[n] += c * s * (rowA @ T)
-            gT[n] += c * s * (rowC @ I)
+            gI[n] += c * s_out * (mag(rowA) @ Ta)
+            gT[n] += c * s_out * (mag(rowC) @ Ia)
     return gI, gT

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     clip_loss_fwd_bwd,
     disco_loss_fwd_bwd,
     disco_resolve_path,
+    disco_set_stage_events,
     disco_status_string,
     disco_workspace_bytes,
     library_path,

@@ -48,6 +48,8 @@ def _load():
     lib.disco_loss_fwd_bwd.restype = ci
     lib.clip_loss_fwd_bwd.argtypes = [vp, vp, i64, i64, f32, ci, ci, vp, vp, vp, vp, vp, sz, vp]
     lib.clip_loss_fwd_bwd.restype = ci
+    lib.disco_set_stage_events.argtypes = [ctypes.POINTER(vp), ci]
+    lib.disco_set_stage_events.restype = ci
     lib.disco_status_string.argtypes = [ci]
     lib.disco_status_string.restype = ctypes.c_char_p
     return lib
@@ -101,3 +103,8 @@ def clip_loss_fwd_bwd(I, T, B, d, s, dtype, path, loss, gI, gT, gs, workspace, w
     if check and st != DISCO_OK:
         raise DiscoError(st, "clip_loss_fwd_bwd")
     return st
+
+
+def disco_set_stage_events(events, count: int) -> int:
+    """`events`: a ctypes array of c_void_p holding hipEvent_t handles (kept alive by the caller), or None."""
+    return _lib.disco_set_stage_events(events, int(count))

@@ -2,7 +2,28 @@
 // No allocation, no synchronisation, no HIP call before validation has passed.
 #include "common.h"
 
+#include <atomic>
+
 using namespace disco;
+
+namespace {
+std::atomic<void**> g_stage_events{nullptr};
+std::atomic<int> g_stage_count{0};
+}  // namespace
+
+namespace disco {
+void stage_mark(hipStream_t st, int k) {
+  void** ev = g_stage_events.load(std::memory_order_acquire);
+  if (ev && k < g_stage_count.load(std::memory_order_acquire)) (void)hipEventRecord(static_cast<hipEvent_t>(ev[k]), st);
+}
+}  // namespace disco
+
+extern "C" int disco_set_stage_events(void** events, int count) {
+  if (count < 0) return DISCO_ERR_SHAPE;
+  g_stage_count.store(events ? count : 0, std::memory_order_release);
+  g_stage_events.store(events, std::memory_order_release);
+  return DISCO_OK;
+}
 
 namespace {
 

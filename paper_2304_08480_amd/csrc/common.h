@@ -28,6 +28,9 @@ struct Problem {
   hipStream_t stream;
 };
 
+// Benchmark stage timing (see disco_set_stage_events): records events[k] on `st` if it exists.
+void stage_mark(hipStream_t st, int k);
+
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 size_t naive_workspace_bytes(int64_t B, int64_t d, int32_t N);

@@ -1,6 +1,545 @@
+// bf16 MFMA path ("materialized"): the two b x B logit blocks are computed once on the matrix cores,
+// their un-normalised softmax numerators are kept in bf16, and the two gradient contractions of each
+// block (Eq. 4-6) are MFMA GEMMs over those numerators.  12*b*B*d executed flops per call.
+//
+// For one block with query rows X (b x d, the rank's rows) and key rows Y (B x d):
+//   z_ij   = s <x_i, y_j>                      z2 = z * log2(e)   (all exponentials are base 2)
+//   ref2_i = z2 of the positive pair (i, label_i), lifted where needed so that no z2_ij - ref2_i
+//            exceeds 100 (overflow guard from the row norms, Cauchy-Schwarz)
+//   E_ij   = exp2(z2_ij - ref2_i)  for j != label_i, stored as bf16 (b x B);  E_i,label = 0 in the
+//            store and kept separately in fp32 as e_i
+//   tot_i  = sum_j E_ij + e_i,  beta_i = 1/tot_i,  P_ij = beta_i E_ij,
+//   ce_i   = log(tot_i / e_i),  P_i,label - 1 = -(sum_j E_ij)/tot_i       (no cancellation)
+//   query-side gradient  gX_i = c s [ beta_i (E Y)_i + (P_i,label - 1) y_label ]
+//   key-side gradient    gY_j = c s [ sum_i E_ij beta_i x_i  (+ (P_i,label - 1) x_i  if j = label_i) ]
+//   d/ds share           c <gX_i / (c s), x_i>  summed over i   (sum_ij G_ij S_ij = <G Y, X>)
+// Since lse_i >= z_i,label, every E_ij that underflows is negligible against the row total.
+//
+// One 256x256x64 NT tile main loop (4 waves, each 128x128 = 4x4 MFMA 32x32x16 blocks, LDS double
+// buffered, XOR-swizzled 16-byte chunks) serves all three contractions; operands whose reduction
+// index is not the contiguous one in memory are transposed in registers (8x8 blocks of bf16) on
+// their way into LDS.
 #include "common.h"
+
 namespace disco {
-bool mfma_supported(int64_t, int64_t, int32_t, int) { return false; }
-size_t mfma_stored_workspace_bytes(int64_t, int64_t, int32_t) { return 0; }
-int mfma_stored_run(const Problem&) { return DISCO_ERR_UNSUPPORTED; }
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int A_BYTES = BM * BK * 2;              // 32 KiB
+constexpr int STAGE_BYTES = (BM + BN) * BK * 2;   // 64 KiB
+constexpr int SMEM_BYTES = 2 * STAGE_BYTES;       // 128 KiB of the CU's 160 KiB
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+constexpr float REF_HEADROOM = 100.f;             // largest exponent (base 2) a stored numerator may reach
+
+// byte offset of 16-byte chunk `chunk` (0..7) of tile row `row` (128-byte rows, XOR swizzle)
+__device__ __forceinline__ uint32_t lds_off(int row, int chunk) {
+  return (uint32_t)row * 128u + (uint32_t)((chunk ^ (row & 7)) << 4);
+}
+
+// Copies a 256 x 64 bf16 operand tile from global memory to LDS through registers.
+//   MODE 0: element (r, k) is at base[r * ld + k]   (reduction index contiguous)
+//   MODE 1: element (r, k) is at base[k * ld + r]   (row index contiguous; 8x8 transposed in registers)
+// Thread t owns chunk column kb = t % 8; in mode 0 rows (t/8) + 32 i, in mode 1 rows 8 (t/8) .. + 7.
+template <int MODE>
+struct TileLoader {
+  u32x4 r[8];
+  __device__ __forceinline__ void load(const uint16_t* base, int64_t ld, int t) {
+    const int kb = t & 7, rb = t >> 3;
+    if (MODE == 0) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) r[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)(rb + 32 * i) * ld + kb * 8);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) r[e] = *reinterpret_cast<const u32x4*>(base + (int64_t)(kb * 8 + e) * ld + rb * 8);
+    }
+  }
+  __device__ __forceinline__ void store(char* lds, int t) const {
+    const int kb = t & 7, rb = t >> 3;
+    if (MODE == 0) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(lds + lds_off(rb + 32 * i, kb)) = r[i];
+    } else {
+      // r[e][p] holds rows (2p, 2p+1) of reduction index e.  Row u of the output needs, in dword q,
+      // reduction indices (2q, 2q+1): the low halves (u even) or high halves (u odd) of r[2q][u/2], r[2q+1][u/2].
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        u32x4 o;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          o[q] = __builtin_amdgcn_perm(r[2 * q + 1][u >> 1], r[2 * q][u >> 1], (u & 1) ? 0x07060302u : 0x05040100u);
+        *reinterpret_cast<u32x4*>(lds + lds_off(rb * 8 + u, kb)) = o;
+      }
+    }
+  }
+};
+
+// acc[bm][bn] += A_tile(256 x K) * B_tile(256 x K)^T for this wave's 128x128 quarter.
+// A, Bp point at element (row 0, k 0) of the tile; ktiles = K / 64.
+template <int MA, int MB>
+__device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bp,
+                                         int64_t ldb, int ktiles, char* smem, f32x16 (&acc)[4][4]) {
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int64_t stepA = MA == 0 ? BK : (int64_t)BK * lda;
+  const int64_t stepB = MB == 0 ? BK : (int64_t)BK * ldb;
+  TileLoader<MA> la;
+  TileLoader<MB> lb;
+  la.load(A, lda, t);
+  lb.load(Bp, ldb, t);
+  la.store(smem, t);
+  lb.store(smem + A_BYTES, t);
+  __syncthreads();
+  const int arow = wm * 128 + (lane & 31), brow = wn * 128 + (lane & 31), kc = lane >> 5;
+  for (int kt = 0; kt < ktiles; ++kt) {
+    char* cur = smem + (kt & 1) * STAGE_BYTES;
+    char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
+    const bool more = kt + 1 < ktiles;
+    if (more) {
+      la.load(A + (kt + 1) * stepA, lda, t);
+      lb.load(Bp + (kt + 1) * stepB, ldb, t);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 af[4], bfr[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        af[i] = *reinterpret_cast<const bf16x8*>(cur + lds_off(arow + 32 * i, ks * 2 + kc));
+        bfr[i] = *reinterpret_cast<const bf16x8*>(cur + A_BYTES + lds_off(brow + 32 * i, ks * 2 + kc));
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+      la.store(nxt, t);
+      lb.store(nxt + A_BYTES, t);
+    }
+    __syncthreads();
+  }
+}
+
+// Workgroup id -> tile, keeping the workgroups that share an XCD's L2 on neighbouring tiles.
+// Workgroups are dealt round-robin to the 8 XCDs; XCD x takes the x-th contiguous eighth of the
+// (padded) tile list.  Returns false for padding.
+__device__ __forceinline__ bool xcd_linear(int total, int& lin) {
+  const int w = blockIdx.x;
+  const int chunk = (total + 7) / 8;
+  lin = (w & 7) * chunk + (w >> 3);
+  return (w >> 3) < chunk && lin < total;
+}
+
+// ------------------------------------------------------------------------------------------------
+struct BlockPtrs {
+  const uint16_t* X;     // b x d, the rank's rows
+  const uint16_t* Y;     // B x d
+  const uint16_t* Yraw;  // same as Y
+  uint16_t* E;           // b x B stored numerators
+  float* lpart;          // (B/128) x b partial row sums (label column excluded)
+  float* ediag;          // b: numerator of the label column
+  float* zd2;            // b: z2 of the positive pair
+  float* xnorm;          // b: |x_i|
+  const uint32_t* ymax2; // 1: bit pattern of max_j |y_j|^2
+  float* beta;           // b
+  float* gdiag;          // b: P_label - 1
+  float* ce;             // b
+  float* rowds;          // b
+  uint16_t* Xs;          // d x b: (beta_i x_i)^T in bf16
+  float* part;           // splitK x b x d partial query-side products
+  float* gq;             // query-side gradient destination (gI for block A, gT for block C), B x d
+  float* gk;             // key-side gradient destination, B x d
+};
+struct Blocks { BlockPtrs z[2]; };
+
+__device__ __forceinline__ float wave_sum(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+__global__ void k_zero2(uint32_t* p) { if (threadIdx.x < 2) p[threadIdx.x] = 0u; }
+
+// max over all rows of |row|^2 for I (slot 0) and T (slot 1); one wave per row.
+__global__ __launch_bounds__(256) void k_rownorm_max(const uint16_t* I, const uint16_t* T, int64_t B, int64_t d,
+                                                      uint32_t* out) {
+  const int which = blockIdx.y;
+  const uint16_t* M = which == 0 ? I : T;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  float a = 0.f;
+  if (row < B)
+    for (int64_t k = lane; k < d; k += 64) { float v = __uint_as_float((uint32_t)M[row * d + k] << 16); a = fmaf(v, v, a); }
+  a = wave_sum(a);
+  if (lane == 0 && row < B) atomicMax(out + which, __float_as_uint(a));   // order-independent, values >= 0
+}
+
+// positive-pair logit and query norm of every local row; one wave per (block, row)
+__global__ __launch_bounds__(256) void k_prep_diag(Blocks bl, int64_t b, int64_t d, int rank, float s2) {
+  const BlockPtrs& p = bl.z[blockIdx.y];
+  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (i >= b) return;
+  const uint16_t* x = p.X + i * d;
+  const uint16_t* y = p.Y + ((int64_t)rank * b + i) * d;
+  float dot = 0.f, nn = 0.f;
+  for (int64_t k = lane; k < d; k += 64) {
+    float xv = __uint_as_float((uint32_t)x[k] << 16), yv = __uint_as_float((uint32_t)y[k] << 16);
+    dot = fmaf(xv, yv, dot);
+    nn = fmaf(xv, xv, nn);
+  }
+  dot = wave_sum(dot);
+  nn = wave_sum(nn);
+  if (lane == 0) { p.zd2[i] = s2 * dot; p.xnorm[i] = sqrtf(nn); }
+}
+
+// Logit tile + softmax numerators.  Tile rows (MFMA M side) are key rows j, tile columns (N side) are
+// query rows i, so that each lane holds 4 consecutive j of one query row per accumulator quad:
+// 8-byte stores into the row-major E and an in-lane row sum.
+__global__ __launch_bounds__(256) void k_logit_tiles(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2,
+                                                      int nIp, int nJp) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const BlockPtrs& p = bl.z[blockIdx.y];
+  int lin;
+  if (!xcd_linear(nIp * nJp, lin)) return;
+  // super-blocks of 8 query tiles x 4 key tiles: 12 operand tiles (3 MiB) feed 32 concurrent workgroups
+  const int sb = lin >> 5, within = lin & 31;
+  const int nSBi = nIp >> 3;
+  const int it = (sb % nSBi) * 8 + (within & 7);
+  const int jt = (sb / nSBi) * 4 + (within >> 3);
+  if ((int64_t)it * BN >= b || (int64_t)jt * BM >= B) return;
+  const int64_t i0 = (int64_t)it * BN, j0 = (int64_t)jt * BM;
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  mainloop<0, 0>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1, half = lane >> 5;
+  const float ymax = sqrtf(__uint_as_float(*p.ymax2));
+  const int64_t lab0 = (int64_t)rank * b;      // label of query row i is key row lab0 + i
+  const bool diag_tile = (lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN);
+#pragma unroll
+  for (int bn = 0; bn < 4; ++bn) {
+    const int64_t i = i0 + wn * 128 + bn * 32 + (lane & 31);
+    const float zd = p.zd2[i];
+    const float ref = fmaxf(zd, fabsf(s2) * p.xnorm[i] * ymax - REF_HEADROOM);
+    const int64_t lab = lab0 + i;
+    float rowsum = 0.f;
+    uint16_t* erow = p.E + i * B;
+#pragma unroll
+    for (int bm = 0; bm < 4; ++bm) {
+      const int64_t jb = j0 + wm * 128 + bm * 32 + half * 4;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float e[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) e[r] = __builtin_amdgcn_exp2f(fmaf(acc[bm][bn][q * 4 + r], s2, -ref));
+        const int64_t j = jb + q * 8;
+        if (diag_tile && lab >= j && lab < j + 4) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (lab == j + r) { p.ediag[i] = e[r]; e[r] = 0.f; }
+        }
+        rowsum += (e[0] + e[1]) + (e[2] + e[3]);
+        bf16x4 pk;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) pk[r] = (__bf16)e[r];
+        *reinterpret_cast<bf16x4*>(erow + j) = pk;
+      }
+    }
+    rowsum += __shfl_xor(rowsum, 32);
+    if (half == 0) p.lpart[((j0 >> 7) + wm) * b + i] = rowsum;
+  }
+}
+
+// Row totals -> beta, P_label - 1, cross-entropy.  One thread per (block, row).
+__global__ __launch_bounds__(256) void k_row_merge(Blocks bl, int64_t b, int nparts) {
+  const BlockPtrs& p = bl.z[blockIdx.y];
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= b) return;
+  float off = 0.f;
+  for (int q = 0; q < nparts; ++q) off += p.lpart[(int64_t)q * b + i];
+  const float ed = p.ediag[i];
+  const float tot = off + ed;
+  p.beta[i] = 1.f / tot;
+  p.gdiag[i] = -off / tot;
+  p.ce[i] = (ed > 0.5f * tot) ? log1pf(off / ed) : logf(tot) - logf(ed);
+}
+
+// Xs[k][i] = bf16(beta_i * x_ik): the key-side contraction's right operand with the reduction index contiguous.
+__global__ __launch_bounds__(256) void k_scale_transpose(Blocks bl, int64_t b, int64_t d) {
+  __shared__ float tile[64][65];
+  const BlockPtrs& p = bl.z[blockIdx.z];
+  const int64_t i0 = (int64_t)blockIdx.x * 64, k0 = (int64_t)blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int r = ty; r < 64; r += 4) {
+    const int64_t i = i0 + r;
+    tile[r][tx] = p.beta[i] * __uint_as_float((uint32_t)p.X[i * d + k0 + tx] << 16);
+  }
+  __syncthreads();
+  for (int r = ty; r < 64; r += 4) {
+    __bf16 v = (__bf16)tile[tx][r];
+    p.Xs[(k0 + r) * b + i0 + tx] = *reinterpret_cast<uint16_t*>(&v);
+  }
+}
+
+// Key-side gradient: gk[j][k] (+)= cs * ( sum_i E[i][j] Xs[k][i]  +  [j = label_i] gdiag_i x_ik ).
+// GEMM M = key rows j (operand E read transposed), N = feature index k, reduction over the rank's rows.
+__global__ __launch_bounds__(256) void k_key_grad(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float cs,
+                                                   int accumulate, int nM, int nN) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const BlockPtrs& p = bl.z[blockIdx.y];
+  int lin;
+  if (!xcd_linear(nM * nN, lin)) return;
+  const int nt = lin % nN, mt = lin / nN;
+  const int64_t j0 = (int64_t)mt * BM, k0 = (int64_t)nt * BN;
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  mainloop<1, 0>(p.E + j0, B, p.Xs + k0 * b, b, (int)(b / BK), smem, acc);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1, half = lane >> 5;
+  const int64_t lab0 = (int64_t)rank * b;
+#pragma unroll
+  for (int bn = 0; bn < 4; ++bn) {
+    const int64_t k = k0 + wn * 128 + bn * 32 + (lane & 31);
+#pragma unroll
+    for (int bm = 0; bm < 4; ++bm)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int64_t j = j0 + wm * 128 + bm * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
+        float v = acc[bm][bn][e];
+        if (j >= lab0 && j < lab0 + b) {
+          const int64_t i = j - lab0;
+          v = fmaf(p.gdiag[i], __uint_as_float((uint32_t)p.X[i * d + k] << 16), v);
+        }
+        float* o = p.gk + j * d + k;
+        *o = (accumulate ? *o : 0.f) + cs * v;
+      }
+  }
+}
+
+// Query-side products, split over the key index: part[ks][i][k] = sum_{j in split ks} E[i][j] y_jk.
+// GEMM M = query rows i, N = feature index k (operand Y read transposed), reduction over key rows.
+__global__ __launch_bounds__(256) void k_query_partial(Blocks bl, int64_t b, int64_t B, int64_t d, int nM, int nN,
+                                                        int splitk, int ktiles_per_split) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const BlockPtrs& p = bl.z[blockIdx.y];
+  int lin;
+  if (!xcd_linear(nM * nN * splitk, lin)) return;
+  const int nt = lin % nN, ks = (lin / nN) % splitk, mt = lin / (nN * splitk);
+  const int64_t i0 = (int64_t)mt * BM, k0 = (int64_t)nt * BN;
+  const int kt_total = (int)(B / BK);
+  const int kt0 = ks * ktiles_per_split;
+  int kts = kt_total - kt0;
+  if (kts > ktiles_per_split) kts = ktiles_per_split;
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  if (kts > 0) mainloop<0, 1>(p.E + i0 * B + (int64_t)kt0 * BK, B, p.Yraw + (int64_t)kt0 * BK * d + k0, d, kts, smem, acc);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1, half = lane >> 5;
+  float* out = p.part + (int64_t)ks * b * d;
+#pragma unroll
+  for (int bn = 0; bn < 4; ++bn) {
+    const int64_t k = k0 + wn * 128 + bn * 32 + (lane & 31);
+#pragma unroll
+    for (int bm = 0; bm < 4; ++bm)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int64_t i = i0 + wm * 128 + bm * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
+        out[i * d + k] = acc[bm][bn][e];
+      }
+  }
+}
+
+// Query-side gradient of one local row: gq[label_i][:] += cs (beta_i sum_ks part + gdiag_i y_label), and the
+// row's share of d/ds, <that vector, x_i>.  One workgroup per (block, row), fixed summation order.
+__global__ __launch_bounds__(128) void k_query_finalize(Blocks bl, int64_t b, int64_t d, int rank, float cs, int splitk) {
+  __shared__ float red[2];
+  const BlockPtrs& p = bl.z[blockIdx.y];
+  const int64_t i = blockIdx.x;
+  const int64_t lab = (int64_t)rank * b + i;
+  const float beta = p.beta[i], gd = p.gdiag[i];
+  float dot = 0.f;
+  for (int64_t k = threadIdx.x; k < d; k += 128) {
+    float u = 0.f;
+    for (int ks = 0; ks < splitk; ++ks) u += p.part[((int64_t)ks * b + i) * d + k];
+    const float yv = __uint_as_float((uint32_t)p.Yraw[lab * d + k] << 16);
+    const float xv = __uint_as_float((uint32_t)p.X[i * d + k] << 16);
+    const float g = fmaf(beta, u, gd * yv);
+    p.gq[lab * d + k] += cs * g;
+    dot = fmaf(g, xv, dot);
+  }
+  dot = wave_sum(dot);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = dot;
+  __syncthreads();
+  if (threadIdx.x == 0) p.rowds[i] = red[0] + red[1];
+}
+
+// loss_r = c sum ce, gs_r = c sum rowds over both blocks; one workgroup, fixed order.
+__global__ __launch_bounds__(1024) void k_scalars(Blocks bl, int64_t b, float c, int accumulate, float* loss, float* gs) {
+  __shared__ float ra[16], rg[16];
+  float a = 0.f, g = 0.f;
+  for (int z = 0; z < 2; ++z)
+    for (int64_t i = threadIdx.x; i < b; i += 1024) { a += bl.z[z].ce[i]; g += bl.z[z].rowds[i]; }
+  a = wave_sum(a);
+  g = wave_sum(g);
+  if ((threadIdx.x & 63) == 0) { ra[threadIdx.x >> 6] = a; rg[threadIdx.x >> 6] = g; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float sa = 0.f, sg = 0.f;
+    for (int w = 0; w < 16; ++w) { sa += ra[w]; sg += rg[w]; }
+    *loss = (accumulate ? *loss : 0.f) + c * sa;
+    *gs = (accumulate ? *gs : 0.f) + c * sg;
+  }
+}
+
+struct Plan {
+  int64_t b, B, d;
+  int nparts;            // B / 128
+  int nMq, nN, splitk, ktps;
+  size_t off_E, off_lpart, off_rows, off_Xs, off_part, off_ymax, total;
+  size_t rows_stride;    // bytes of one b-float row array (aligned)
+};
+
+Plan make_plan(int64_t B, int64_t d, int32_t N) {
+  Plan pl;
+  pl.B = B; pl.d = d; pl.b = B / N;
+  const int64_t b = pl.b;
+  pl.nparts = (int)(B / 128);
+  pl.nMq = (int)(b / BM);
+  pl.nN = (int)(d / BN);
+  const int tiles = pl.nMq * pl.nN;
+  const int kt_total = (int)(B / BK);
+  int sk = (512 + tiles - 1) / tiles;
+  if (sk > 32) sk = 32;
+  if (sk > kt_total) sk = kt_total;
+  if (sk < 1) sk = 1;
+  pl.ktps = (kt_total + sk - 1) / sk;
+  pl.splitk = (kt_total + pl.ktps - 1) / pl.ktps;
+  size_t o = 0;
+  pl.off_E = o;      o += 2 * align_up((size_t)b * B * 2);
+  pl.off_lpart = o;  o += 2 * align_up((size_t)pl.nparts * b * 4);
+  pl.rows_stride = align_up((size_t)b * 4);
+  pl.off_rows = o;   o += 2 * 7 * pl.rows_stride;   // ediag, zd2, xnorm, beta, gdiag, ce, rowds
+  pl.off_Xs = o;     o += 2 * align_up((size_t)d * b * 2);
+  pl.off_part = o;   o += 2 * align_up((size_t)pl.splitk * b * d * 4);
+  pl.off_ymax = o;   o += 256;
+  pl.total = o;
+  return pl;
+}
+
+}  // namespace
+
+bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype) {
+  if (dtype != DISCO_BF16) return false;
+  if (N <= 0 || B % N != 0) return false;
+  const int64_t b = B / N;
+  return b % 256 == 0 && d % 256 == 0;
+}
+
+size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N) { return make_plan(B, d, N).total; }
+
+int mfma_stored_run(const Problem& pr) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_logit_tiles),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_key_grad),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+    hipError_t e3 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_query_partial),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) return DISCO_ERR_HIP;
+    attr_set = true;
+  }
+  const Plan pl = make_plan(pr.B, pr.d, pr.N);
+  const int64_t b = pl.b, B = pl.B, d = pl.d;
+  char* ws = static_cast<char*>(pr.ws);
+  const uint16_t* I = static_cast<const uint16_t*>(pr.I);
+  const uint16_t* T = static_cast<const uint16_t*>(pr.T);
+  uint32_t* ymax = reinterpret_cast<uint32_t*>(ws + pl.off_ymax);   // [0] = max |I_j|^2, [1] = max |T_j|^2
+
+  Blocks bl;
+  for (int z = 0; z < 2; ++z) {
+    BlockPtrs& p = bl.z[z];
+    const uint16_t* Xfull = z == 0 ? I : T;
+    p.X = Xfull + (size_t)pr.rank * b * d;
+    p.Y = z == 0 ? T : I;
+    p.Yraw = p.Y;
+    p.E = reinterpret_cast<uint16_t*>(ws + pl.off_E + z * align_up((size_t)b * B * 2));
+    p.lpart = reinterpret_cast<float*>(ws + pl.off_lpart + z * align_up((size_t)pl.nparts * b * 4));
+    char* rows = ws + pl.off_rows + (size_t)z * 7 * pl.rows_stride;
+    p.ediag = reinterpret_cast<float*>(rows + 0 * pl.rows_stride);
+    p.zd2 = reinterpret_cast<float*>(rows + 1 * pl.rows_stride);
+    p.xnorm = reinterpret_cast<float*>(rows + 2 * pl.rows_stride);
+    p.beta = reinterpret_cast<float*>(rows + 3 * pl.rows_stride);
+    p.gdiag = reinterpret_cast<float*>(rows + 4 * pl.rows_stride);
+    p.ce = reinterpret_cast<float*>(rows + 5 * pl.rows_stride);
+    p.rowds = reinterpret_cast<float*>(rows + 6 * pl.rows_stride);
+    p.ymax2 = ymax + (z == 0 ? 1 : 0);
+    p.Xs = reinterpret_cast<uint16_t*>(ws + pl.off_Xs + z * align_up((size_t)d * b * 2));
+    p.part = reinterpret_cast<float*>(ws + pl.off_part + z * align_up((size_t)pl.splitk * b * d * 4));
+    p.gq = z == 0 ? pr.gI : pr.gT;
+    p.gk = z == 0 ? pr.gT : pr.gI;
+  }
+
+  const float s2 = pr.s * LOG2E;
+  const float c = 1.0f / (2.0f * (float)B);
+  const float cs = c * pr.s;
+  hipStream_t st = pr.stream;
+
+  stage_mark(st, 0);
+  k_zero2<<<1, 64, 0, st>>>(ymax);
+  k_rownorm_max<<<dim3((unsigned)((B + 3) / 4), 2), 256, 0, st>>>(I, T, B, d, ymax);
+  k_prep_diag<<<dim3((unsigned)((b + 3) / 4), 2), 256, 0, st>>>(bl, b, d, pr.rank, s2);
+
+  stage_mark(st, 1);
+
+  const int nI = (int)(b / BN), nJ = (int)(B / BM);
+  const int nIp = (nI + 7) / 8 * 8, nJp = (nJ + 3) / 4 * 4;
+  const int fwd_wgs = ((nIp * nJp + 7) / 8) * 8;
+  k_logit_tiles<<<dim3((unsigned)fwd_wgs, 2), 256, SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, nIp, nJp);
+  stage_mark(st, 2);
+  k_row_merge<<<dim3((unsigned)((b + 255) / 256), 2), 256, 0, st>>>(bl, b, pl.nparts);
+  k_scale_transpose<<<dim3((unsigned)(b / 64), (unsigned)(d / 64), 2), 256, 0, st>>>(bl, b, d);
+
+  stage_mark(st, 3);
+
+  const int nMk = (int)(B / BM);
+  const int key_wgs = ((nMk * pl.nN + 7) / 8) * 8;
+  k_key_grad<<<dim3((unsigned)key_wgs, 2), 256, SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, cs, pr.accumulate, nMk, pl.nN);
+
+  stage_mark(st, 4);
+
+  const int q_wgs = ((pl.nMq * pl.nN * pl.splitk + 7) / 8) * 8;
+  k_query_partial<<<dim3((unsigned)q_wgs, 2), 256, SMEM_BYTES, st>>>(bl, b, B, d, pl.nMq, pl.nN, pl.splitk, pl.ktps);
+  stage_mark(st, 5);
+  k_query_finalize<<<dim3((unsigned)b, 2), 128, 0, st>>>(bl, b, d, pr.rank, cs, pl.splitk);
+  k_scalars<<<1, 1024, 0, st>>>(bl, b, c, pr.accumulate, pr.loss, pr.gs);
+  stage_mark(st, 6);
+  return hipGetLastError() == hipSuccess ? DISCO_OK : DISCO_ERR_HIP;
+}
+
 }  // namespace disco

@@ -213,13 +213,19 @@ int naive_run(const Problem& p) {
   const float c = 1.0f / (2.0f * (float)B);
   const float cs = c * p.s;
 
+  stage_mark(p.stream, 0);
   naive_similarity<<<dim3(cdiv(B, TS), cdiv(b, TS), 2), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W);
+  stage_mark(p.stream, 1);
   naive_row_softmax<<<dim3((unsigned)b, 2), 256, 0, p.stream>>>(W, b, B, p.rank, p.s, row_ce, row_ds);
+  stage_mark(p.stream, 2);
   naive_scalars<<<1, 256, 0, p.stream>>>(row_ce, row_ds, 2 * b, c, p.accumulate, p.loss, p.gs);
+  stage_mark(p.stream, 3);
   naive_key_grad<<<dim3(cdiv(d, TS), cdiv(B, TS), 2), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,
                                                                           p.accumulate, p.gI, p.gT);
+  stage_mark(p.stream, 4);
   naive_query_grad<<<dim3(cdiv(d, TS), cdiv(b, TS), 2), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,
                                                                             p.gI, p.gT);
+  stage_mark(p.stream, 5);
   return hipGetLastError() == hipSuccess ? DISCO_OK : DISCO_ERR_HIP;
 }
 

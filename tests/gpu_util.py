@@ -13,6 +13,12 @@ def to_device(I_f32, T_f32, I_bits, T_bits, dtype):
     return torch.from_numpy(I_f32).cuda(), torch.from_numpy(T_f32).cuda(), dl.DISCO_F32
 
 
+def term_scale(oc, I, T, s, rank, N):
+    """(scale_gI, scale_gT, oracle_floor) for check_tensor."""
+    sI, sT = oc.disco_rank_term_scale(I, T, s, rank, N)
+    return sI, sT, 1e-13 * abs(s) / (2.0 * I.shape[0])
+
+
 class Runner:
     """Owns outputs and workspace for one (B, d, N, dtype, path)."""
 
@@ -42,29 +48,49 @@ class Runner:
                 self.gT.cpu().numpy().astype(np.float64), float(self.gs.item()))
 
 
-# Tolerances.  fp32 inputs: relative 1e-4.  bf16 inputs with fp32 accumulation: relative 2e-2 with an
-# absolute floor of 1e-3 of the tensor's largest magnitude on gradients.  Gradient entries are of size
-# 1/(2B) and smaller, so the absolute part is expressed relative to max|ref|.
+# Tolerances.
+# Scalars (loss, d/ds) and the Frobenius-relative error of each gradient tensor use the stated bars:
+# 1e-4 for fp32 inputs, 2e-2 for bf16 inputs with fp32 accumulation.  (The loss never sees a bf16
+# rounding, its row sums are fp32, so it keeps 1e-4 in both; d/ds gets ten times the loss bar.)
+# The stated absolute floor for bf16 gradients, 1e-3, is larger than any gradient entry (they are of
+# size 1/(2B) and below), so it is asserted but decides nothing.  The elementwise bound that does
+# decide is derived from the arithmetic: every gradient entry is a sum of products, and on the bf16
+# path each factor of each product is rounded to bf16 once (8 significant bits, unit roundoff u = 2^-8), so
+#     |error_ik| <= 2u * sum_j |term_ijk|  (1 + o(1))
+# whatever cancels in the sum.  The sum of term magnitudes comes from the oracle
+# (disco_rank_term_scale); k = 2u with 10% slack = 8.6e-3.  On the fp32 path the same sum bounds the
+# accumulation error: k = 1e-5 (about 2^-24 * sqrt(terms) with slack) next to the stated 1e-4 * |ref|.
 TOL = {
-    "f32": dict(scalar=1e-4, frob=1e-4, rel=1e-4, abs_of_max=1e-5),
-    "bf16": dict(scalar=2e-3, frob=2e-2, rel=2e-2, abs_of_max=1e-3),
+    "f32": dict(scalar=1e-4, frob=1e-4, rel=1e-4, k_scale=1e-5),
+    "bf16": dict(scalar=1e-4, frob=2e-2, rel=0.0, k_scale=8.6e-3),
 }
 
 
-def check_scalar(name, got, ref, tol, floor=1e-30):
-    err = abs(got - ref) / max(abs(ref), floor)
-    assert np.isfinite(got) and err <= tol, f"{name}: got {got!r} ref {ref!r} rel err {err:.3e} > {tol}"
-    return err
+def check_scalar(name, got, ref, tol, abs_tol=1e-12):
+    """|got - ref| <= tol * |ref| + abs_tol.  abs_tol covers the oracle's own float64 cancellation when the
+    softmax saturates (s = 100: lse - z_label is a difference of numbers near 100, good to ~1e-14 per row)."""
+    err = abs(got - ref)
+    assert np.isfinite(got) and err <= tol * abs(ref) + abs_tol, \
+        f"{name}: got {got!r} ref {ref!r} abs err {err:.3e} > {tol} * |ref| + {abs_tol}"
+    return err / max(abs(ref), abs_tol)
 
 
-def check_tensor(name, got, ref, kind):
+def check_tensor(name, got, ref, kind, scale, oracle_floor=0.0):
+    """Frobenius-relative error against the stated bar, and the derived elementwise bound.
+
+    oracle_floor: absolute per-entry uncertainty of the float64 oracle itself.  It forms P_label - 1 by
+    subtraction, so when the softmax saturates (P_label = 1 - 1e-29 at s = 100) its gradient entries are
+    rounding noise of size 2^-53 * c * s rather than the true 1e-30; callers pass 1e-13 * c * s.
+    """
     t = TOL[kind]
     assert np.isfinite(got).all(), f"{name}: non-finite values"
     diff = np.abs(got - ref)
-    mx = np.abs(ref).max()
-    fro = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300)
-    bound = t["abs_of_max"] * mx + t["rel"] * np.abs(ref)
-    worst = (diff - bound).max()
-    assert fro <= t["frob"], f"{name}: Frobenius rel err {fro:.3e} > {t['frob']}"
-    assert worst <= 0, f"{name}: elementwise bound exceeded by {worst:.3e} (max|ref| {mx:.3e}, max diff {diff.max():.3e})"
-    return fro, diff.max() / max(mx, 1e-300)
+    nd, nr = np.linalg.norm(got - ref), np.linalg.norm(ref)
+    fro = nd / max(nr, 1e-300)
+    assert nd <= t["frob"] * nr + oracle_floor * np.sqrt(ref.size), f"{name}: Frobenius rel err {fro:.3e} > {t['frob']}"
+    bound = t["rel"] * np.abs(ref) + t["k_scale"] * scale + oracle_floor + 1e-300
+    ratio = (diff / bound).max()
+    assert ratio <= 1.0, f"{name}: elementwise error reaches {ratio:.2f} x its bound (max diff {diff.max():.3e})"
+    if kind == "bf16":
+        assert (diff <= 1e-3 + 2e-2 * np.abs(ref)).all()      # the stated form, literally
+    return fro, ratio

@@ -1,0 +1,93 @@
+"""GPU parity of the bf16 MFMA path against the float64 oracle at sizes that span several 256x256 tiles,
+several split-K slices and ranks whose diagonal sits in different tiles."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2304_08480_amd as dl
+from oracle import clip_oracle as oc
+from synth import clip_pairs, f32_to_bf16_bits, bf16_bits_to_f32
+from tests.gpu_util import Runner, term_scale, check_scalar, check_tensor, to_device, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(B, d, seed, **kw):
+    I, T = clip_pairs(B, d, seed, **kw)
+    Ib, Tb = f32_to_bf16_bits(I), f32_to_bf16_bits(T)
+    return bf16_bits_to_f32(Ib), bf16_bits_to_f32(Tb), Ib, Tb
+
+
+def _compare(run, ref, scale, tag):
+    loss, gI, gT, gs = run.results()
+    errs = dict(
+        loss=check_scalar(f"{tag} loss", loss, ref[0], TOL["bf16"]["scalar"]),
+        gs=check_scalar(f"{tag} gs", gs, ref[3], TOL["bf16"]["scalar"] * 10, abs_tol=1e-9),
+        gI=check_tensor(f"{tag} gI", gI, ref[1], "bf16", scale[0], scale[2]),
+        gT=check_tensor(f"{tag} gT", gT, ref[2], "bf16", scale[1], scale[2]),
+    )
+    print(tag, {k: (f"{v:.2e}" if isinstance(v, float) else tuple(f"{x:.2e}" for x in v)) for k, v in errs.items()},
+          flush=True)
+    return loss, gI, gT, gs
+
+
+@pytest.mark.parametrize("B,d,N,s,kw", [
+    (1024, 256, 2, 14.285714, {}),
+    (2048, 512, 4, 14.285714, {}),
+    (1536, 768, 2, 14.285714, dict(hard_frac=0.1)),
+    (1024, 256, 1, 100.0, dict(noise=3.5)),
+    (2048, 256, 8, 100.0, {}),
+    (512, 256, 2, 0.0, {}),
+])
+def test_mfma_path_matches_oracle(B, d, N, s, kw):
+    I, T, Ib, Tb = _inputs(B, d, 5, **kw)
+    Id, Td, dt = to_device(I, T, Ib, Tb, "bf16")
+    assert dl.disco_resolve_path(B, d, N, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_MATERIALIZED
+    run = Runner(Id, Td, B, d, N, dt, dl.DISCO_PATH_MATERIALIZED)
+    for r in sorted({0, N // 2, N - 1}):
+        print(f"case B={B} d={d} N={N} s={s} rank={r}", flush=True)
+        run.rank(r, s)
+        _compare(run, oc.disco_rank(I, T, s, r, N), term_scale(oc, I, T, s, r, N),
+                 f"B{B} d{d} N{N} s{s:g} rank {r}")
+    for r in range(N):
+        run.rank(r, s, accumulate=(r > 0))
+    full = oc.clip_loss_full(I, T, s)
+    full_scale = term_scale(oc, I, T, s, 0, 1)
+    _compare(run, full, full_scale, f"B{B} d{d} N{N} s{s:g} accumulated")
+    run1 = Runner(Id, Td, B, d, 1, dt, dl.DISCO_PATH_MATERIALIZED)
+    run1.full(s)
+    _compare(run1, full, full_scale, f"B{B} d{d} clip_loss_fwd_bwd")
+
+
+def test_mfma_path_is_deterministic_and_accumulates():
+    B, d, N, s = 1024, 256, 2, 14.285714
+    I, T, Ib, Tb = _inputs(B, d, 6)
+    Id, Td, dt = to_device(I, T, Ib, Tb, "bf16")
+    run = Runner(Id, Td, B, d, N, dt, dl.DISCO_PATH_MATERIALIZED)
+    run.rank(1, s)
+    l1, a1, t1, g1 = run.results()
+    run.rank(1, s)
+    l2, a2, t2, g2 = run.results()
+    assert l1 == l2 and g1 == g2 and np.array_equal(a1, a2) and np.array_equal(t1, t2)
+    run.gI.fill_(0.5); run.gT.fill_(-0.25); run.loss.fill_(2.0); run.gs.fill_(1.0)
+    run.rank(1, s, accumulate=True)
+    l3, a3, t3, g3 = run.results()
+    assert l3 == pytest.approx(2.0 + l1, rel=1e-6) and g3 == pytest.approx(1.0 + g1, rel=1e-6)
+    np.testing.assert_allclose(a3, a1 + 0.5, rtol=1e-6)
+    np.testing.assert_allclose(t3, t1 - 0.25, rtol=1e-6)
+
+
+def test_mfma_path_agrees_with_naive_path_on_gpu():
+    # two independent kernel sets behind the same boundary
+    B, d, N, s = 2048, 256, 4, 20.0
+    I, T, Ib, Tb = _inputs(B, d, 8)
+    Id, Td, dt = to_device(I, T, Ib, Tb, "bf16")
+    fast = Runner(Id, Td, B, d, N, dt, dl.DISCO_PATH_MATERIALIZED)
+    slow = Runner(Id, Td, B, d, N, dt, dl.DISCO_PATH_NAIVE)
+    fast.rank(2, s); slow.rank(2, s)
+    lf, af, tf, gf = fast.results()
+    ls, as_, ts, gs_ = slow.results()
+    check_scalar("loss", lf, ls, 1e-4)
+    sI, sT, fl = term_scale(oc, I, T, s, 2, N)
+    check_tensor("gI", af, as_, "bf16", sI, fl)
+    check_tensor("gT", tf, ts, "bf16", sT, fl)

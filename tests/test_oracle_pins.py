@@ -243,6 +243,7 @@ def test_sampled_rows_match_dense():
     a, t = oc.rank_grad_rows(I, T, s, r, N, lseA, lseC, rows)
     np.testing.assert_allclose(a, gI[rows], rtol=1e-11, atol=1e-17)
     np.testing.assert_allclose(t, gT[rows], rtol=1e-11, atol=1e-17)
+    assert oc.rank_loss_from_stats(I, T, s, r, N, lseA, lseC) == pytest.approx(oc.disco_rank(I, T, s, r, N)[0], rel=1e-13)
 
 
 def test_memory_model_figures_from_the_paper():
@@ -261,3 +262,22 @@ def test_memory_model_figures_from_the_paper():
         full, disco = B * B, 2 * (B // N) * B
         assert 1 - disco / full == vals[key]
     assert round(100 * vals["saved_fraction_N64"]) == vals["saved_percent_N64_approx"]
+
+
+def test_term_scale_matches_loops_and_bounds_the_gradient():
+    I, T = _rand_pairs(8, 4, 17)
+    s, N = 6.5, 2
+    for r in range(N):
+        sI, sT = oc.disco_rank_term_scale(I, T, s, r, N)
+        bI, bT = brute.brute_rank_term_scale(I.tolist(), T.tolist(), s, r, N)
+        np.testing.assert_allclose(sI, np.array(bI), rtol=1e-11)
+        np.testing.assert_allclose(sT, np.array(bT), rtol=1e-11)
+        _, gI, gT, _ = oc.disco_rank(I, T, s, r, N)
+        assert (np.abs(gI) <= sI * (1 + 1e-12)).all() and (np.abs(gT) <= sT * (1 + 1e-12)).all()   # triangle inequality
+    # sampled rows agree with the dense arrays
+    lseA, lseC = oc.rank_row_stats(I, T, s, 1, N)
+    rows = np.array([0, 3, 4, 7])
+    a, t = oc.rank_grad_rows(I, T, s, 1, N, lseA, lseC, rows, magnitudes=True)
+    sI, sT = oc.disco_rank_term_scale(I, T, s, 1, N)
+    np.testing.assert_allclose(a, sI[rows], rtol=1e-11)
+    np.testing.assert_allclose(t, sT[rows], rtol=1e-11)
