@@ -20,111 +20,16 @@
 // index is not the contiguous one in memory are transposed in registers (8x8 blocks of bf16) on
 // their way into LDS.
 #include "common.h"
+#include "mfma_tile.h"
 
 namespace disco {
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+using namespace tile;
 
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int A_BYTES = BM * BK * 2;              // 32 KiB
-constexpr int STAGE_BYTES = (BM + BN) * BK * 2;   // 64 KiB
-constexpr int SMEM_BYTES = 2 * STAGE_BYTES;       // 128 KiB of the CU's 160 KiB
-constexpr float LOG2E = 1.4426950408889634f;
-constexpr float LN2 = 0.6931471805599453f;
-constexpr float REF_HEADROOM = 100.f;             // largest exponent (base 2) a stored numerator may reach
-
-// byte offset of 16-byte chunk `chunk` (0..7) of tile row `row` (128-byte rows, XOR swizzle)
-__device__ __forceinline__ uint32_t lds_off(int row, int chunk) {
-  return (uint32_t)row * 128u + (uint32_t)((chunk ^ (row & 7)) << 4);
-}
-
-// Copies a 256 x 64 bf16 operand tile from global memory to LDS through registers.
-//   MODE 0: element (r, k) is at base[r * ld + k]   (reduction index contiguous)
-//   MODE 1: element (r, k) is at base[k * ld + r]   (row index contiguous; 8x8 transposed in registers)
-// Thread t owns chunk column kb = t % 8; in mode 0 rows (t/8) + 32 i, in mode 1 rows 8 (t/8) .. + 7.
-template <int MODE>
-struct TileLoader {
-  u32x4 r[8];
-  __device__ __forceinline__ void load(const uint16_t* base, int64_t ld, int t) {
-    const int kb = t & 7, rb = t >> 3;
-    if (MODE == 0) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) r[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)(rb + 32 * i) * ld + kb * 8);
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) r[e] = *reinterpret_cast<const u32x4*>(base + (int64_t)(kb * 8 + e) * ld + rb * 8);
-    }
-  }
-  __device__ __forceinline__ void store(char* lds, int t) const {
-    const int kb = t & 7, rb = t >> 3;
-    if (MODE == 0) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(lds + lds_off(rb + 32 * i, kb)) = r[i];
-    } else {
-      // r[e][p] holds rows (2p, 2p+1) of reduction index e.  Row u of the output needs, in dword q,
-      // reduction indices (2q, 2q+1): the low halves (u even) or high halves (u odd) of r[2q][u/2], r[2q+1][u/2].
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        u32x4 o;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          o[q] = __builtin_amdgcn_perm(r[2 * q + 1][u >> 1], r[2 * q][u >> 1], (u & 1) ? 0x07060302u : 0x05040100u);
-        *reinterpret_cast<u32x4*>(lds + lds_off(rb * 8 + u, kb)) = o;
-      }
-    }
-  }
-};
-
-// acc[bm][bn] += A_tile(256 x K) * B_tile(256 x K)^T for this wave's 128x128 quarter.
-// A, Bp point at element (row 0, k 0) of the tile; ktiles = K / 64.
-template <int MA, int MB>
-__device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bp,
-                                         int64_t ldb, int ktiles, char* smem, f32x16 (&acc)[4][4]) {
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int64_t stepA = MA == 0 ? BK : (int64_t)BK * lda;
-  const int64_t stepB = MB == 0 ? BK : (int64_t)BK * ldb;
-  TileLoader<MA> la;
-  TileLoader<MB> lb;
-  la.load(A, lda, t);
-  lb.load(Bp, ldb, t);
-  la.store(smem, t);
-  lb.store(smem + A_BYTES, t);
-  __syncthreads();
-  const int arow = wm * 128 + (lane & 31), brow = wn * 128 + (lane & 31), kc = lane >> 5;
-  for (int kt = 0; kt < ktiles; ++kt) {
-    char* cur = smem + (kt & 1) * STAGE_BYTES;
-    char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-    const bool more = kt + 1 < ktiles;
-    if (more) {
-      la.load(A + (kt + 1) * stepA, lda, t);
-      lb.load(Bp + (kt + 1) * stepB, ldb, t);
-    }
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 af[4], bfr[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        af[i] = *reinterpret_cast<const bf16x8*>(cur + lds_off(arow + 32 * i, ks * 2 + kc));
-        bfr[i] = *reinterpret_cast<const bf16x8*>(cur + A_BYTES + lds_off(brow + 32 * i, ks * 2 + kc));
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    if (more) {
-      la.store(nxt, t);
-      lb.store(nxt + A_BYTES, t);
-    }
-    __syncthreads();
-  }
-}
+constexpr int E_ROW_BYTES = BM * 2 + 16;                 // padded row of the staged numerator tile
+constexpr int E_TILE_BYTES = BN * E_ROW_BYTES;            // 132 KiB
+constexpr int LOGIT_SMEM_BYTES = E_TILE_BYTES > SMEM_BYTES ? E_TILE_BYTES : SMEM_BYTES;
 
 // Workgroup id -> tile, keeping the workgroups that share an XCD's L2 on neighbouring tiles.
 // Workgroups are dealt round-robin to the 8 XCDs; XCD x takes the x-th contiguous eighth of the
@@ -165,18 +70,31 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 __global__ void k_zero2(uint32_t* p) { if (threadIdx.x < 2) p[threadIdx.x] = 0u; }
 
-// max over all rows of |row|^2 for I (slot 0) and T (slot 1); one wave per row.
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// max over all rows of |row|^2 for I (slot 0) and T (slot 1).  One wave per row at a time (16-byte
+// loads, d is a multiple of 8), grid-stride over rows, one atomicMax per workgroup (max is
+// order-independent, so the result is deterministic; values are >= 0 so the bit patterns order like floats).
 __global__ __launch_bounds__(256) void k_rownorm_max(const uint16_t* I, const uint16_t* T, int64_t B, int64_t d,
                                                       uint32_t* out) {
+  __shared__ float red[4];
   const int which = blockIdx.y;
   const uint16_t* M = which == 0 ? I : T;
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
-  float a = 0.f;
-  if (row < B)
-    for (int64_t k = lane; k < d; k += 64) { float v = __uint_as_float((uint32_t)M[row * d + k] << 16); a = fmaf(v, v, a); }
-  a = wave_sum(a);
-  if (lane == 0 && row < B) atomicMax(out + which, __float_as_uint(a));   // order-independent, values >= 0
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float best = 0.f;
+  for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < B; row += (int64_t)gridDim.x * 4) {
+    float a = 0.f;
+    for (int64_t k = lane * 8; k < d; k += 512) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(M + row * d + k);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { a = fmaf(bf16_lo(v[q]), bf16_lo(v[q]), a); a = fmaf(bf16_hi(v[q]), bf16_hi(v[q]), a); }
+    }
+    best = fmaxf(best, wave_sum(a));
+  }
+  if (lane == 0) red[wave] = best;
+  __syncthreads();
+  if (threadIdx.x == 0) atomicMax(out + which, __float_as_uint(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]))));
 }
 
 // positive-pair logit and query norm of every local row; one wave per (block, row)
@@ -229,23 +147,29 @@ __global__ __launch_bounds__(256) void k_logit_tiles(Blocks bl, int64_t b, int64
   const float ymax = sqrtf(__uint_as_float(*p.ymax2));
   const int64_t lab0 = (int64_t)rank * b;      // label of query row i is key row lab0 + i
   const bool diag_tile = (lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN);
+  // The numerators leave through LDS: each lane holds 4 consecutive key columns of 32 different query
+  // rows, which as direct global stores would be 16-byte fragments; staged as a row-major 256 x 256 bf16
+  // tile (rows padded to 528 bytes: conflict-free 8-byte writes and 16-byte reads) they go out as whole
+  // 512-byte row segments.
+  lds_barrier();                               // every wave is done with the operand buffers
 #pragma unroll
   for (int bn = 0; bn < 4; ++bn) {
-    const int64_t i = i0 + wn * 128 + bn * 32 + (lane & 31);
+    const int il = wn * 128 + bn * 32 + (lane & 31);
+    const int64_t i = i0 + il;
     const float zd = p.zd2[i];
     const float ref = fmaxf(zd, fabsf(s2) * p.xnorm[i] * ymax - REF_HEADROOM);
     const int64_t lab = lab0 + i;
     float rowsum = 0.f;
-    uint16_t* erow = p.E + i * B;
+    char* lrow = smem + il * E_ROW_BYTES;
 #pragma unroll
     for (int bm = 0; bm < 4; ++bm) {
-      const int64_t jb = j0 + wm * 128 + bm * 32 + half * 4;
+      const int jl = wm * 128 + bm * 32 + half * 4;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         float e[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) e[r] = __builtin_amdgcn_exp2f(fmaf(acc[bm][bn][q * 4 + r], s2, -ref));
-        const int64_t j = jb + q * 8;
+        const int64_t j = j0 + jl + q * 8;
         if (diag_tile && lab >= j && lab < j + 4) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
@@ -255,21 +179,47 @@ __global__ __launch_bounds__(256) void k_logit_tiles(Blocks bl, int64_t b, int64
         bf16x4 pk;
 #pragma unroll
         for (int r = 0; r < 4; ++r) pk[r] = (__bf16)e[r];
-        *reinterpret_cast<bf16x4*>(erow + j) = pk;
+        *reinterpret_cast<bf16x4*>(lrow + (jl + q * 8) * 2) = pk;
       }
     }
     rowsum += __shfl_xor(rowsum, 32);
     if (half == 0) p.lpart[((j0 >> 7) + wm) * b + i] = rowsum;
   }
+  lds_barrier();
+  {
+    const int t = threadIdx.x;
+    const int chunk = t & 31, r0 = t >> 5;     // 32 chunks of 16 bytes per 512-byte row; 8 rows per pass
+#pragma unroll 8
+    for (int r = 0; r < 32; ++r) {
+      const int row = r * 8 + r0;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + chunk * 16);
+      *reinterpret_cast<u32x4*>(p.E + (i0 + row) * B + j0 + chunk * 8) = v;
+    }
+  }
 }
 
-// Row totals -> beta, P_label - 1, cross-entropy.  One thread per (block, row).
+// Row totals -> beta, P_label - 1, cross-entropy.  A workgroup takes 64 rows; its 4 waves each add a
+// quarter of the column parts (lane = row, so the reads are coalesced), combined in fixed order.
 __global__ __launch_bounds__(256) void k_row_merge(Blocks bl, int64_t b, int nparts) {
+  __shared__ float red[4][64];
   const BlockPtrs& p = bl.z[blockIdx.y];
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= b) return;
-  float off = 0.f;
-  for (int q = 0; q < nparts; ++q) off += p.lpart[(int64_t)q * b + i];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t i = (int64_t)blockIdx.x * 64 + lane;
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  if (i < b) {
+    int q = wave;
+    for (; q + 12 < nparts; q += 16) {
+      a0 += p.lpart[(int64_t)q * b + i];
+      a1 += p.lpart[(int64_t)(q + 4) * b + i];
+      a2 += p.lpart[(int64_t)(q + 8) * b + i];
+      a3 += p.lpart[(int64_t)(q + 12) * b + i];
+    }
+    for (; q < nparts; q += 4) a0 += p.lpart[(int64_t)q * b + i];
+  }
+  red[wave][lane] = (a0 + a1) + (a2 + a3);
+  __syncthreads();
+  if (wave != 0 || i >= b) return;
+  const float off = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
   const float ed = p.ediag[i];
   const float tot = off + ed;
   p.beta[i] = 1.f / tot;
@@ -294,10 +244,11 @@ __global__ __launch_bounds__(256) void k_scale_transpose(Blocks bl, int64_t b, i
   }
 }
 
-// Key-side gradient: gk[j][k] (+)= cs * ( sum_i E[i][j] Xs[k][i]  +  [j = label_i] gdiag_i x_ik ).
+// Key-side gradient without its label-column term: gk[j][k] (+)= cs * sum_i E[i][j] Xs[k][i].
+// (The term [j = label_i] gdiag_i x_ik is added by k_query_finalize, which owns the rank's rows.)
 // GEMM M = key rows j (operand E read transposed), N = feature index k, reduction over the rank's rows.
-__global__ __launch_bounds__(256) void k_key_grad(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float cs,
-                                                   int accumulate, int nM, int nN) {
+template <bool ACCUMULATE>
+__global__ __launch_bounds__(256) void k_key_grad(Blocks bl, int64_t b, int64_t B, int64_t d, float cs, int nM, int nN) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const BlockPtrs& p = bl.z[blockIdx.y];
   int lin;
@@ -315,23 +266,19 @@ __global__ __launch_bounds__(256) void k_key_grad(Blocks bl, int64_t b, int64_t 
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1, half = lane >> 5;
-  const int64_t lab0 = (int64_t)rank * b;
 #pragma unroll
   for (int bn = 0; bn < 4; ++bn) {
     const int64_t k = k0 + wn * 128 + bn * 32 + (lane & 31);
 #pragma unroll
-    for (int bm = 0; bm < 4; ++bm)
+    for (int bm = 0; bm < 4; ++bm) {
+      float* o = p.gk + (j0 + wm * 128 + bm * 32 + half * 4) * d + k;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int64_t j = j0 + wm * 128 + bm * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
-        float v = acc[bm][bn][e];
-        if (j >= lab0 && j < lab0 + b) {
-          const int64_t i = j - lab0;
-          v = fmaf(p.gdiag[i], __uint_as_float((uint32_t)p.X[i * d + k] << 16), v);
-        }
-        float* o = p.gk + j * d + k;
-        *o = (accumulate ? *o : 0.f) + cs * v;
+        float* oe = o + ((e >> 2) * 8 + (e & 3)) * d;
+        if (ACCUMULATE) *oe = fmaf(cs, acc[bm][bn][e], *oe);
+        else *oe = cs * acc[bm][bn][e];
       }
+    }
   }
 }
 
@@ -374,28 +321,39 @@ __global__ __launch_bounds__(256) void k_query_partial(Blocks bl, int64_t b, int
   }
 }
 
-// Query-side gradient of one local row: gq[label_i][:] += cs (beta_i sum_ks part + gdiag_i y_label), and the
-// row's share of d/ds, <that vector, x_i>.  One workgroup per (block, row), fixed summation order.
-__global__ __launch_bounds__(128) void k_query_finalize(Blocks bl, int64_t b, int64_t d, int rank, float cs, int splitk) {
-  __shared__ float red[2];
-  const BlockPtrs& p = bl.z[blockIdx.y];
-  const int64_t i = blockIdx.x;
+// Query-side gradient of one local row: gq[label_i][:] += cs (beta_i sum_ks part + gdiag_i y_label), the
+// label-column term of the key-side gradient gk[label_i][:] += cs gdiag_i x_i, and the row's share of
+// d/ds, <query-side vector, x_i>.  Block A's gq is block C's gk, so the two blocks run one after the other.  One workgroup per (block, row), fixed summation order.
+__global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int z, int64_t b, int64_t d, int rank, float cs, int splitk) {
+  typedef __attribute__((ext_vector_type(4))) float f32x4;
+  const BlockPtrs& p = bl.z[z];
+  const int lane = threadIdx.x & 63;
+  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // one wave per local row
+  if (i >= b) return;
   const int64_t lab = (int64_t)rank * b + i;
   const float beta = p.beta[i], gd = p.gdiag[i];
   float dot = 0.f;
-  for (int64_t k = threadIdx.x; k < d; k += 128) {
-    float u = 0.f;
-    for (int ks = 0; ks < splitk; ++ks) u += p.part[((int64_t)ks * b + i) * d + k];
-    const float yv = __uint_as_float((uint32_t)p.Yraw[lab * d + k] << 16);
-    const float xv = __uint_as_float((uint32_t)p.X[i * d + k] << 16);
-    const float g = fmaf(beta, u, gd * yv);
-    p.gq[lab * d + k] += cs * g;
-    dot = fmaf(g, xv, dot);
+  for (int64_t k = lane * 4; k < d; k += 256) {
+    f32x4 u = {0.f, 0.f, 0.f, 0.f};
+    for (int ks = 0; ks < splitk; ++ks) u += *reinterpret_cast<const f32x4*>(p.part + ((int64_t)ks * b + i) * d + k);
+    const u32x2 yw = *reinterpret_cast<const u32x2*>(p.Yraw + lab * d + k);
+    const u32x2 xw = *reinterpret_cast<const u32x2*>(p.X + i * d + k);
+    const float yv[4] = {bf16_lo(yw[0]), bf16_hi(yw[0]), bf16_lo(yw[1]), bf16_hi(yw[1])};
+    const float xv[4] = {bf16_lo(xw[0]), bf16_hi(xw[0]), bf16_lo(xw[1]), bf16_hi(xw[1])};
+    f32x4 gq = *reinterpret_cast<f32x4*>(p.gq + lab * d + k);
+    f32x4 gk = *reinterpret_cast<f32x4*>(p.gk + lab * d + k);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float g = fmaf(beta, u[e], gd * yv[e]);
+      gq[e] = fmaf(cs, g, gq[e]);
+      gk[e] = fmaf(cs * gd, xv[e], gk[e]);      // label-column term of the key-side gradient
+      dot = fmaf(g, xv[e], dot);
+    }
+    *reinterpret_cast<f32x4*>(p.gq + lab * d + k) = gq;
+    *reinterpret_cast<f32x4*>(p.gk + lab * d + k) = gk;
   }
   dot = wave_sum(dot);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = dot;
-  __syncthreads();
-  if (threadIdx.x == 0) p.rowds[i] = red[0] + red[1];
+  if (lane == 0) p.rowds[i] = dot;
 }
 
 // loss_r = c sum ce, gs_r = c sum rowds over both blocks; one workgroup, fixed order.
@@ -466,12 +424,14 @@ int mfma_stored_run(const Problem& pr) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_logit_tiles),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, LOGIT_SMEM_BYTES);
+    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_key_grad<false>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
-    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_key_grad),
+    hipError_t e4 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_key_grad<true>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
     hipError_t e3 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_query_partial),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
-    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) return DISCO_ERR_HIP;
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess) return DISCO_ERR_HIP;
     attr_set = true;
   }
   const Plan pl = make_plan(pr.B, pr.d, pr.N);
@@ -512,7 +472,7 @@ int mfma_stored_run(const Problem& pr) {
 
   stage_mark(st, 0);
   k_zero2<<<1, 64, 0, st>>>(ymax);
-  k_rownorm_max<<<dim3((unsigned)((B + 3) / 4), 2), 256, 0, st>>>(I, T, B, d, ymax);
+  k_rownorm_max<<<dim3((unsigned)((B + 3) / 4 < 1024 ? (B + 3) / 4 : 1024), 2), 256, 0, st>>>(I, T, B, d, ymax);
   k_prep_diag<<<dim3((unsigned)((b + 3) / 4), 2), 256, 0, st>>>(bl, b, d, pr.rank, s2);
 
   stage_mark(st, 1);
@@ -520,23 +480,27 @@ int mfma_stored_run(const Problem& pr) {
   const int nI = (int)(b / BN), nJ = (int)(B / BM);
   const int nIp = (nI + 7) / 8 * 8, nJp = (nJ + 3) / 4 * 4;
   const int fwd_wgs = ((nIp * nJp + 7) / 8) * 8;
-  k_logit_tiles<<<dim3((unsigned)fwd_wgs, 2), 256, SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, nIp, nJp);
+  k_logit_tiles<<<dim3((unsigned)fwd_wgs, 2), 256, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, nIp, nJp);
   stage_mark(st, 2);
-  k_row_merge<<<dim3((unsigned)((b + 255) / 256), 2), 256, 0, st>>>(bl, b, pl.nparts);
+  k_row_merge<<<dim3((unsigned)((b + 63) / 64), 2), 256, 0, st>>>(bl, b, pl.nparts);
   k_scale_transpose<<<dim3((unsigned)(b / 64), (unsigned)(d / 64), 2), 256, 0, st>>>(bl, b, d);
 
   stage_mark(st, 3);
 
   const int nMk = (int)(B / BM);
   const int key_wgs = ((nMk * pl.nN + 7) / 8) * 8;
-  k_key_grad<<<dim3((unsigned)key_wgs, 2), 256, SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, cs, pr.accumulate, nMk, pl.nN);
+  if (pr.accumulate)
+    k_key_grad<true><<<dim3((unsigned)key_wgs, 2), 256, SMEM_BYTES, st>>>(bl, b, B, d, cs, nMk, pl.nN);
+  else
+    k_key_grad<false><<<dim3((unsigned)key_wgs, 2), 256, SMEM_BYTES, st>>>(bl, b, B, d, cs, nMk, pl.nN);
 
   stage_mark(st, 4);
 
   const int q_wgs = ((pl.nMq * pl.nN * pl.splitk + 7) / 8) * 8;
   k_query_partial<<<dim3((unsigned)q_wgs, 2), 256, SMEM_BYTES, st>>>(bl, b, B, d, pl.nMq, pl.nN, pl.splitk, pl.ktps);
   stage_mark(st, 5);
-  k_query_finalize<<<dim3((unsigned)b, 2), 128, 0, st>>>(bl, b, d, pr.rank, cs, pl.splitk);
+  k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, 0, b, d, pr.rank, cs, pl.splitk);
+  k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, 1, b, d, pr.rank, cs, pl.splitk);
   k_scalars<<<1, 1024, 0, st>>>(bl, b, c, pr.accumulate, pr.loss, pr.gs);
   stage_mark(st, 6);
   return hipGetLastError() == hipSuccess ? DISCO_OK : DISCO_ERR_HIP;
