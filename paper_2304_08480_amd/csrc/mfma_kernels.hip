@@ -27,9 +27,13 @@ namespace {
 
 using namespace tile;
 
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float REF_HEADROOM = 100.f;                    // largest exponent (base 2) a stored numerator may reach
+
 constexpr int E_ROW_BYTES = BM * 2 + 16;                 // padded row of the staged numerator tile
 constexpr int E_TILE_BYTES = BN * E_ROW_BYTES;            // 132 KiB
 constexpr int LOGIT_SMEM_BYTES = E_TILE_BYTES > SMEM_BYTES ? E_TILE_BYTES : SMEM_BYTES;
+constexpr int GEMM_SMEM_BYTES = OUT_SMEM_BYTES > SMEM_BYTES ? OUT_SMEM_BYTES : SMEM_BYTES;
 
 // Workgroup id -> tile, keeping the workgroups that share an XCD's L2 on neighbouring tiles.
 // Workgroups are dealt round-robin to the 8 XCDs; XCD x takes the x-th contiguous eighth of the
@@ -263,23 +267,7 @@ __global__ __launch_bounds__(256) void k_key_grad(Blocks bl, int64_t b, int64_t 
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   mainloop<1, 0>(p.E + j0, B, p.Xs + k0 * b, b, (int)(b / BK), smem, acc);
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1, half = lane >> 5;
-#pragma unroll
-  for (int bn = 0; bn < 4; ++bn) {
-    const int64_t k = k0 + wn * 128 + bn * 32 + (lane & 31);
-#pragma unroll
-    for (int bm = 0; bm < 4; ++bm) {
-      float* o = p.gk + (j0 + wm * 128 + bm * 32 + half * 4) * d + k;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float* oe = o + ((e >> 2) * 8 + (e & 3)) * d;
-        if (ACCUMULATE) *oe = fmaf(cs, acc[bm][bn][e], *oe);
-        else *oe = cs * acc[bm][bn][e];
-      }
-    }
-  }
+  store_tile_f32<ACCUMULATE>(acc, smem, p.gk + j0 * d + k0, d, cs);
 }
 
 // Query-side products, split over the key index: part[ks][i][k] = sum_{j in split ks} E[i][j] y_jk.
@@ -304,21 +292,7 @@ __global__ __launch_bounds__(256) void k_query_partial(Blocks bl, int64_t b, int
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   if (kts > 0) mainloop<0, 1>(p.E + i0 * B + (int64_t)kt0 * BK, B, p.Yraw + (int64_t)kt0 * BK * d + k0, d, kts, smem, acc);
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1, half = lane >> 5;
-  float* out = p.part + (int64_t)ks * b * d;
-#pragma unroll
-  for (int bn = 0; bn < 4; ++bn) {
-    const int64_t k = k0 + wn * 128 + bn * 32 + (lane & 31);
-#pragma unroll
-    for (int bm = 0; bm < 4; ++bm)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int64_t i = i0 + wm * 128 + bm * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
-        out[i * d + k] = acc[bm][bn][e];
-      }
-  }
+  store_tile_f32<false>(acc, smem, p.part + (int64_t)ks * b * d + i0 * d + k0, d, 1.0f);
 }
 
 // Query-side gradient of one local row: gq[label_i][:] += cs (beta_i sum_ks part + gdiag_i y_label), the
@@ -391,11 +365,12 @@ Plan make_plan(int64_t B, int64_t d, int32_t N) {
   pl.nN = (int)(d / BN);
   const int tiles = pl.nMq * pl.nN;
   const int kt_total = (int)(B / BK);
-  int sk = (512 + tiles - 1) / tiles;
+  int sk = (256 + tiles - 1) / tiles;      // one workgroup per compute unit
   if (sk > 32) sk = 32;
   if (sk > kt_total) sk = kt_total;
   if (sk < 1) sk = 1;
   pl.ktps = (kt_total + sk - 1) / sk;
+  pl.ktps += pl.ktps & 1;                  // the tile main loop takes K-steps in pairs (kt_total is a multiple of 8)
   pl.splitk = (kt_total + pl.ktps - 1) / pl.ktps;
   size_t o = 0;
   pl.off_E = o;      o += 2 * align_up((size_t)b * B * 2);
@@ -426,11 +401,11 @@ int mfma_stored_run(const Problem& pr) {
     hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_logit_tiles),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, LOGIT_SMEM_BYTES);
     hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_key_grad<false>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_SMEM_BYTES);
     hipError_t e4 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_key_grad<true>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_SMEM_BYTES);
     hipError_t e3 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_query_partial),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_SMEM_BYTES);
     if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess) return DISCO_ERR_HIP;
     attr_set = true;
   }
@@ -490,14 +465,14 @@ int mfma_stored_run(const Problem& pr) {
   const int nMk = (int)(B / BM);
   const int key_wgs = ((nMk * pl.nN + 7) / 8) * 8;
   if (pr.accumulate)
-    k_key_grad<true><<<dim3((unsigned)key_wgs, 2), 256, SMEM_BYTES, st>>>(bl, b, B, d, cs, nMk, pl.nN);
+    k_key_grad<true><<<dim3((unsigned)key_wgs, 2), 256, GEMM_SMEM_BYTES, st>>>(bl, b, B, d, cs, nMk, pl.nN);
   else
-    k_key_grad<false><<<dim3((unsigned)key_wgs, 2), 256, SMEM_BYTES, st>>>(bl, b, B, d, cs, nMk, pl.nN);
+    k_key_grad<false><<<dim3((unsigned)key_wgs, 2), 256, GEMM_SMEM_BYTES, st>>>(bl, b, B, d, cs, nMk, pl.nN);
 
   stage_mark(st, 4);
 
   const int q_wgs = ((pl.nMq * pl.nN * pl.splitk + 7) / 8) * 8;
-  k_query_partial<<<dim3((unsigned)q_wgs, 2), 256, SMEM_BYTES, st>>>(bl, b, B, d, pl.nMq, pl.nN, pl.splitk, pl.ktps);
+  k_query_partial<<<dim3((unsigned)q_wgs, 2), 256, GEMM_SMEM_BYTES, st>>>(bl, b, B, d, pl.nMq, pl.nN, pl.splitk, pl.ktps);
   stage_mark(st, 5);
   k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, 0, b, d, pr.rank, cs, pl.splitk);
   k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, 1, b, d, pr.rank, cs, pl.splitk);
