@@ -15,10 +15,9 @@
 //   d/ds share           c <gX_i / (c s), x_i>  summed over i   (sum_ij G_ij S_ij = <G Y, X>)
 // Since lse_i >= z_i,label, every E_ij that underflows is negligible against the row total.
 //
-// One 256x256x64 NT tile main loop (4 waves, each 128x128 = 4x4 MFMA 32x32x16 blocks, LDS double
-// buffered, XOR-swizzled 16-byte chunks) serves all three contractions; operands whose reduction
-// index is not the contiguous one in memory are transposed in registers (8x8 blocks of bf16) on
-// their way into LDS.
+// One 256x256x32 NT tile main loop (8 waves, each 128x64 = 4x2 MFMA 32x32x16 blocks, four LDS stages,
+// swizzled 16-byte chunks) serves all three contractions; operands whose reduction index is not the
+// contiguous one in memory are transposed in registers (4x4 blocks of bf16) on their way into LDS.
 #include "common.h"
 #include "mfma_tile.h"
 
@@ -123,7 +122,7 @@ __global__ __launch_bounds__(256) void k_prep_diag(Blocks bl, int64_t b, int64_t
 // Logit tile + softmax numerators.  Tile rows (MFMA M side) are key rows j, tile columns (N side) are
 // query rows i, so that each lane holds 4 consecutive j of one query row per accumulator quad:
 // 8-byte stores into the row-major E and an in-lane row sum.
-__global__ __launch_bounds__(256) void k_logit_tiles(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2,
+__global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2,
                                                       int nIp, int nJp) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const BlockPtrs& p = bl.z[blockIdx.y];
@@ -137,17 +136,17 @@ __global__ __launch_bounds__(256) void k_logit_tiles(Blocks bl, int64_t b, int64
   if ((int64_t)it * BN >= b || (int64_t)jt * BM >= B) return;
   const int64_t i0 = (int64_t)it * BN, j0 = (int64_t)jt * BM;
 
-  f32x16 acc[4][4];
+  f32x16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   mainloop<0, 0>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1, half = lane >> 5;
+  const int wm = wave >> 2, wn = wave & 3, half = lane >> 5;
   const float ymax = sqrtf(__uint_as_float(*p.ymax2));
   const int64_t lab0 = (int64_t)rank * b;      // label of query row i is key row lab0 + i
   const bool diag_tile = (lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN);
@@ -157,8 +156,8 @@ __global__ __launch_bounds__(256) void k_logit_tiles(Blocks bl, int64_t b, int64
   // 512-byte row segments.
   lds_barrier();                               // every wave is done with the operand buffers
 #pragma unroll
-  for (int bn = 0; bn < 4; ++bn) {
-    const int il = wn * 128 + bn * 32 + (lane & 31);
+  for (int bn = 0; bn < 2; ++bn) {
+    const int il = wn * 64 + bn * 32 + (lane & 31);
     const int64_t i = i0 + il;
     const float zd = p.zd2[i];
     const float ref = fmaxf(zd, fabsf(s2) * p.xnorm[i] * ymax - REF_HEADROOM);
@@ -192,10 +191,10 @@ __global__ __launch_bounds__(256) void k_logit_tiles(Blocks bl, int64_t b, int64
   lds_barrier();
   {
     const int t = threadIdx.x;
-    const int chunk = t & 31, r0 = t >> 5;     // 32 chunks of 16 bytes per 512-byte row; 8 rows per pass
+    const int chunk = t & 31, r0 = t >> 5;     // 32 chunks of 16 bytes per 512-byte row; 16 rows per pass
 #pragma unroll 8
-    for (int r = 0; r < 32; ++r) {
-      const int row = r * 8 + r0;
+    for (int r = 0; r < 16; ++r) {
+      const int row = r * 16 + r0;
       const u32x4 v = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + chunk * 16);
       *reinterpret_cast<u32x4*>(p.E + (i0 + row) * B + j0 + chunk * 8) = v;
     }
@@ -252,18 +251,18 @@ __global__ __launch_bounds__(256) void k_scale_transpose(Blocks bl, int64_t b, i
 // (The term [j = label_i] gdiag_i x_ik is added by k_query_finalize, which owns the rank's rows.)
 // GEMM M = key rows j (operand E read transposed), N = feature index k, reduction over the rank's rows.
 template <bool ACCUMULATE>
-__global__ __launch_bounds__(256) void k_key_grad(Blocks bl, int64_t b, int64_t B, int64_t d, float cs, int nM, int nN) {
+__global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int64_t B, int64_t d, float cs, int nM, int nN) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const BlockPtrs& p = bl.z[blockIdx.y];
   int lin;
   if (!xcd_linear(nM * nN, lin)) return;
   const int nt = lin % nN, mt = lin / nN;
   const int64_t j0 = (int64_t)mt * BM, k0 = (int64_t)nt * BN;
-  f32x16 acc[4][4];
+  f32x16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   mainloop<1, 0>(p.E + j0, B, p.Xs + k0 * b, b, (int)(b / BK), smem, acc);
@@ -272,7 +271,7 @@ __global__ __launch_bounds__(256) void k_key_grad(Blocks bl, int64_t b, int64_t 
 
 // Query-side products, split over the key index: part[ks][i][k] = sum_{j in split ks} E[i][j] y_jk.
 // GEMM M = query rows i, N = feature index k (operand Y read transposed), reduction over key rows.
-__global__ __launch_bounds__(256) void k_query_partial(Blocks bl, int64_t b, int64_t B, int64_t d, int nM, int nN,
+__global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b, int64_t B, int64_t d, int nM, int nN,
                                                         int splitk, int ktiles_per_split) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const BlockPtrs& p = bl.z[blockIdx.y];
@@ -284,11 +283,11 @@ __global__ __launch_bounds__(256) void k_query_partial(Blocks bl, int64_t b, int
   const int kt0 = ks * ktiles_per_split;
   int kts = kt_total - kt0;
   if (kts > ktiles_per_split) kts = ktiles_per_split;
-  f32x16 acc[4][4];
+  f32x16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   if (kts > 0) mainloop<0, 1>(p.E + i0 * B + (int64_t)kt0 * BK, B, p.Yraw + (int64_t)kt0 * BK * d + k0, d, kts, smem, acc);
@@ -455,7 +454,7 @@ int mfma_stored_run(const Problem& pr) {
   const int nI = (int)(b / BN), nJ = (int)(B / BM);
   const int nIp = (nI + 7) / 8 * 8, nJp = (nJ + 3) / 4 * 4;
   const int fwd_wgs = ((nIp * nJp + 7) / 8) * 8;
-  k_logit_tiles<<<dim3((unsigned)fwd_wgs, 2), 256, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, nIp, nJp);
+  k_logit_tiles<<<dim3((unsigned)fwd_wgs, 2), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, nIp, nJp);
   stage_mark(st, 2);
   k_row_merge<<<dim3((unsigned)((b + 63) / 64), 2), 256, 0, st>>>(bl, b, pl.nparts);
   k_scale_transpose<<<dim3((unsigned)(b / 64), (unsigned)(d / 64), 2), 256, 0, st>>>(bl, b, d);
@@ -465,14 +464,14 @@ int mfma_stored_run(const Problem& pr) {
   const int nMk = (int)(B / BM);
   const int key_wgs = ((nMk * pl.nN + 7) / 8) * 8;
   if (pr.accumulate)
-    k_key_grad<true><<<dim3((unsigned)key_wgs, 2), 256, GEMM_SMEM_BYTES, st>>>(bl, b, B, d, cs, nMk, pl.nN);
+    k_key_grad<true><<<dim3((unsigned)key_wgs, 2), NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, B, d, cs, nMk, pl.nN);
   else
-    k_key_grad<false><<<dim3((unsigned)key_wgs, 2), 256, GEMM_SMEM_BYTES, st>>>(bl, b, B, d, cs, nMk, pl.nN);
+    k_key_grad<false><<<dim3((unsigned)key_wgs, 2), NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, B, d, cs, nMk, pl.nN);
 
   stage_mark(st, 4);
 
   const int q_wgs = ((pl.nMq * pl.nN * pl.splitk + 7) / 8) * 8;
-  k_query_partial<<<dim3((unsigned)q_wgs, 2), 256, GEMM_SMEM_BYTES, st>>>(bl, b, B, d, pl.nMq, pl.nN, pl.splitk, pl.ktps);
+  k_query_partial<<<dim3((unsigned)q_wgs, 2), NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, B, d, pl.nMq, pl.nN, pl.splitk, pl.ktps);
   stage_mark(st, 5);
   k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, 0, b, d, pr.rank, cs, pl.splitk);
   k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, 1, b, d, pr.rank, cs, pl.splitk);

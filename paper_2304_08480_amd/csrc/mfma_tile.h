@@ -1,6 +1,11 @@
-// Device-side building blocks of the bf16 MFMA path: the 256x256x64 NT tile main loop
-// (4 waves, each 128x128 = 4x4 MFMA 32x32x16 blocks, LDS double buffered, XOR-swizzled 16-byte
-// chunks) and the operand tile loaders.  Included by mfma_kernels.hip only.
+// Device-side building blocks of the bf16 MFMA path: the 256x256x32 NT tile main loop (8 waves = two
+// per SIMD, each 128x64 = 4x2 MFMA 32x32x16 blocks, four LDS stages, swizzled 16-byte chunks), the
+// operand tile loaders and the LDS-staged tile store.  Included by mfma_kernels.hip only.
+//
+// Why two waves per SIMD: a wave issues its instructions strictly one after the other, and an LDS write
+// or a global load keeps it busy for tens of cycles, so a lone wave cannot hide them behind its own
+// MFMAs (measured: their costs simply add up).  With a second wave on the SIMD the matrix pipe takes
+// MFMAs from one wave while the other issues memory instructions.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -14,6 +19,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
+constexpr int NTHREADS = 512;                     // 8 waves: 2 (M) x 4 (N), wave tile 128 x 64
 constexpr int BM = 256, BN = 256, BK = 32;
 constexpr int NSTAGE = 4;
 constexpr int A_BYTES = BM * BK * 2;              // 16 KiB
@@ -21,62 +27,70 @@ constexpr int STAGE_BYTES = (BM + BN) * BK * 2;   // 32 KiB
 constexpr int SMEM_BYTES = NSTAGE * STAGE_BYTES;  // 128 KiB of the CU's 160 KiB
 
 // Byte offset of 16-byte chunk `chunk` (0..3) of tile row `row` (64-byte rows: 32 bf16 of the reduction
-// index).  The LDS has 64 banks of 4 bytes, so four consecutive rows span all banks once; XOR-ing the
-// chunk with bits 2..3 of the row makes the 16 rows that a quarter-wave reads for an MFMA operand (same
-// chunk, consecutive rows) hit 16 different 16-byte bank groups.
+// index).  The LDS has 64 banks of 4 bytes, so four consecutive rows span all banks once.  Two
+// permutations keep every access pattern below conflict-free:
+//   * the chunk is XOR-ed with bits 2..3 of the row, so the 16 consecutive rows that a quarter-wave reads
+//     for an MFMA operand (same chunk) hit 16 different 16-byte bank groups;
+//   * the two low row bits are XOR-ed with bits 2..3 as well, so rows that are 4 apart (what neighbouring
+//     lanes of the transposing loader write) fall into different quarters of the banks.
 __device__ __forceinline__ uint32_t lds_off(int row, int chunk) {
-  return (uint32_t)row * 64u + (uint32_t)((chunk ^ ((row >> 2) & 3)) << 4);
+  const int g = (row >> 2) & 3;
+  return (uint32_t)(row ^ g) * 64u + (uint32_t)((chunk ^ g) << 4);
 }
 
-// Copies a 256 x 32 bf16 operand tile from global memory to LDS through registers.
-//   MODE 0: element (r, k) is at base[r * ld + k]   (reduction index contiguous): 16-byte loads, thread t
-//           owns chunk t % 4 of rows t/4 + 64 i;
-//   MODE 1: element (r, k) is at base[k * ld + r]   (row index contiguous): thread t loads an 8 (k) x 4 (r)
-//           block with 8-byte loads, transposes it in registers and writes 4 rows of 16 bytes.
+// Copies a 256 x 32 bf16 operand tile from global memory to LDS through registers (512 threads).
+//   MODE 0: element (r, k) is at base[r * ld + k]   (reduction index contiguous): two 16-byte loads,
+//           thread t owns chunk t % 4 of rows t/4 and t/4 + 128;
+//   MODE 1: element (r, k) is at base[k * ld + r]   (row index contiguous): thread t loads a 4 (k) x 4 (r)
+//           block with four 8-byte loads, transposes it in registers and writes four 8-byte row pieces.
 template <int MODE>
 struct TileLoader {
-  u32x4 r[4];
+  u32x2 r[4];      // MODE 0: two 16-byte chunks as (r[0], r[1]) and (r[2], r[3]); MODE 1: four 8-byte rows
   uint32_t voff;   // this thread's byte offset inside the tile; everything else in an address is wave-uniform
   __device__ __forceinline__ void init(int64_t ld, int t) {
-    const int kb = t & 3, rb = t >> 2;
-    voff = MODE == 0 ? (uint32_t)((rb * ld + kb * 8) * 2) : (uint32_t)((kb * 8 * ld + rb * 4) * 2);
+    if (MODE == 0) voff = (uint32_t)(((t >> 2) * ld + (t & 3) * 8) * 2);
+    else voff = (uint32_t)(((t & 7) * 4 * ld + (t >> 3) * 4) * 2);
   }
   // base: wave-uniform pointer to element (row 0, k 0) of the tile's current K-step
   __device__ __forceinline__ void load(const uint16_t* base, int64_t ld) {
     if (MODE == 0) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        r[i] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(base + (int64_t)(64 * i) * ld) + voff);
+      for (int i = 0; i < 2; ++i) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(base + (int64_t)(128 * i) * ld) + voff);
+        r[2 * i][0] = v[0]; r[2 * i][1] = v[1]; r[2 * i + 1][0] = v[2]; r[2 * i + 1][1] = v[3];
+      }
     } else {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const u32x2 v = *reinterpret_cast<const u32x2*>(reinterpret_cast<const char*>(base + (int64_t)e * ld) + voff);
-        r[e >> 1][(e & 1) * 2] = v[0];
-        r[e >> 1][(e & 1) * 2 + 1] = v[1];
-      }
+      for (int e = 0; e < 4; ++e)
+        r[e] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const char*>(base + (int64_t)e * ld) + voff);
     }
   }
   __device__ __forceinline__ void store(char* lds, int t) const {
-    const int kb = t & 3, rb = t >> 2;
     if (MODE == 0) {
+      const int kb = t & 3, rb = t >> 2;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(lds + lds_off(rb + 64 * i, kb)) = r[i];
+      for (int i = 0; i < 2; ++i) {
+        u32x4 v;
+        v[0] = r[2 * i][0]; v[1] = r[2 * i][1]; v[2] = r[2 * i + 1][0]; v[3] = r[2 * i + 1][1];
+        *reinterpret_cast<u32x4*>(lds + lds_off(rb + 128 * i, kb)) = v;
+      }
     } else {
-      // reduction index e lives in r[e/2][(e%2)*2 + p], p = row pair (rows 2p, 2p+1 in the low/high half).
-      // Row u of the output needs, in dword q, reduction indices (2q, 2q+1) of row u.
+      // r[e] = (rows 0,1 | rows 2,3) of reduction index 4 kq + e.  Output row u needs reduction indices
+      // (0,1) in its first dword and (2,3) in its second: low halves for even u, high halves for odd u.
+      const int kq = t & 7, rq = t >> 3;
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        u32x4 o;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          o[q] = __builtin_amdgcn_perm(r[q][2 + (u >> 1)], r[q][u >> 1], (u & 1) ? 0x07060302u : 0x05040100u);
-        *reinterpret_cast<u32x4*>(lds + lds_off(rb * 4 + u, kb)) = o;
+        const uint32_t sel = (u & 1) ? 0x07060302u : 0x05040100u;
+        u32x2 o;
+        o[0] = __builtin_amdgcn_perm(r[1][u >> 1], r[0][u >> 1], sel);
+        o[1] = __builtin_amdgcn_perm(r[3][u >> 1], r[2][u >> 1], sel);
+        *reinterpret_cast<u32x2*>(lds + lds_off(rq * 4 + u, kq >> 1) + (kq & 1) * 8) = o;
       }
     }
   }
 };
 
-// acc[bm][bn] += A_tile(256 x K) * B_tile(256 x K)^T for this wave's 128x128 quarter.
+// acc[bm][bn] += A_tile(256 x K) * B_tile(256 x K)^T for this wave's 128 x 64 piece.
 // A, Bp point at element (row 0, k 0) of the tile; ktiles = K / 32, which must be even and positive.
 //
 // Software pipeline.  Four LDS stages of one 32-wide K-step each and two register sets:
@@ -85,10 +99,9 @@ struct TileLoader {
 //   barrier (LDS traffic only, never the global loads);
 //   step kt, sub-step 1: MFMAs; fetch the first fragments of step kt+1 from its stage; write the other
 //                        register set (K-step kt+2, loaded during step kt-1) into stage (kt+2) % 4.
-// Every sub-step therefore carries 16 MFMAs, 8 LDS reads and 8 loads or LDS writes: no bursts.  A global
-// load has one and a half steps to land; an LDS stage is complete a full step before it is read and is
-// not overwritten until two barriers after its last reader.  Loads past the end are clamped to the last
-// K-step (redundant, never out of range).
+// A global load has one and a half steps to land; an LDS stage is complete a full step before it is read
+// and is not overwritten until two barriers after its last reader.  Loads past the end are clamped to
+// the last K-step (redundant, never out of range).
 #define DISCO_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 constexpr int SG_MFMA = 0x008, SG_VMEM_RD = 0x020, SG_DS_RD = 0x100, SG_DS_WR = 0x200;
 
@@ -96,16 +109,17 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 
 template <int MA, int MB>
 __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bp,
-                                         int64_t ldb, int ktiles, char* smem, f32x16 (&acc)[4][4]) {
+                                         int64_t ldb, int ktiles, char* smem, f32x16 (&acc)[4][2]) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int64_t stepA = MA == 0 ? BK : (int64_t)BK * lda;
   const int64_t stepB = MB == 0 ? BK : (int64_t)BK * ldb;
   const int last = ktiles - 1;
-  const int arow = (wave >> 1) * 128 + (lane & 31), brow = (wave & 1) * 128 + (lane & 31), kc = lane >> 5;
+  const int arow = (wave >> 2) * 128 + (lane & 31), brow = (wave & 3) * 64 + (lane & 31), kc = lane >> 5;
+  constexpr int NLD = (MA == 0 ? 2 : 4) + (MB == 0 ? 2 : 4);   // global loads / LDS writes per thread and K-step
   TileLoader<MA> la0, la1;
   TileLoader<MB> lb0, lb1;
   la0.init(lda, t); la1.init(lda, t); lb0.init(ldb, t); lb1.init(ldb, t);
-  bf16x8 af0[4], bf0[4], af1[4], bf1[4];
+  bf16x8 af0[4], bf0[2], af1[4], bf1[2];
 
   // prologue: K-steps 0 and 1 into stages 0 and 1, K-step 2 into register set 1
   la0.load(A, lda);
@@ -126,10 +140,9 @@ __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A, int64_t
   }
   lds_barrier();
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    af0[i] = *reinterpret_cast<const bf16x8*>(smem + lds_off(arow + 32 * i, kc));
-    bf0[i] = *reinterpret_cast<const bf16x8*>(smem + A_BYTES + lds_off(brow + 32 * i, kc));
-  }
+  for (int i = 0; i < 4; ++i) af0[i] = *reinterpret_cast<const bf16x8*>(smem + lds_off(arow + 32 * i, kc));
+#pragma unroll
+  for (int i = 0; i < 2; ++i) bf0[i] = *reinterpret_cast<const bf16x8*>(smem + A_BYTES + lds_off(brow + 32 * i, kc));
 
   // one K-step: loads go into (la_new, lb_new), LDS writes come from (la_old, lb_old)
   auto step = [&](int kt, TileLoader<MA>& la_new, TileLoader<MB>& lb_new, const TileLoader<MA>& la_old,
@@ -140,39 +153,37 @@ __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A, int64_t
     const int kload = kt + 3 < ktiles ? kt + 3 : last;
     // sub-step 0
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      af1[i] = *reinterpret_cast<const bf16x8*>(cur + lds_off(arow + 32 * i, 2 + kc));
-      bf1[i] = *reinterpret_cast<const bf16x8*>(cur + A_BYTES + lds_off(brow + 32 * i, 2 + kc));
-    }
+    for (int i = 0; i < 4; ++i) af1[i] = *reinterpret_cast<const bf16x8*>(cur + lds_off(arow + 32 * i, 2 + kc));
+#pragma unroll
+    for (int i = 0; i < 2; ++i) bf1[i] = *reinterpret_cast<const bf16x8*>(cur + A_BYTES + lds_off(brow + 32 * i, 2 + kc));
     la_new.load(A + kload * stepA, lda);
     lb_new.load(Bp + kload * stepB, ldb);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af0[i], bf0[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af0[i], bf0[j], acc[i][j], 0, 0, 0);
 #pragma unroll
-    for (int g = 0; g < 4; ++g) { DISCO_SGB(SG_DS_RD, 2); DISCO_SGB(SG_MFMA, 2); }
-#pragma unroll
-    for (int g = 0; g < 4; ++g) { DISCO_SGB(SG_VMEM_RD, (MA == 0 ? 1 : 2) + (MB == 0 ? 1 : 2)); DISCO_SGB(SG_MFMA, 2); }
+    for (int g = 0; g < 3; ++g) { DISCO_SGB(SG_DS_RD, 2); DISCO_SGB(SG_MFMA, 1); }
+    DISCO_SGB(SG_VMEM_RD, NLD / 2); DISCO_SGB(SG_MFMA, 2);
+    DISCO_SGB(SG_VMEM_RD, NLD - NLD / 2); DISCO_SGB(SG_MFMA, 3);
     __builtin_amdgcn_sched_barrier(0);   // nothing moves between sub-steps
     // sub-step 1
     lds_barrier();
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      af0[i] = *reinterpret_cast<const bf16x8*>(nxt + lds_off(arow + 32 * i, kc));
-      bf0[i] = *reinterpret_cast<const bf16x8*>(nxt + A_BYTES + lds_off(brow + 32 * i, kc));
-    }
+    for (int i = 0; i < 4; ++i) af0[i] = *reinterpret_cast<const bf16x8*>(nxt + lds_off(arow + 32 * i, kc));
+#pragma unroll
+    for (int i = 0; i < 2; ++i) bf0[i] = *reinterpret_cast<const bf16x8*>(nxt + A_BYTES + lds_off(brow + 32 * i, kc));
     la_old.store(wr, t);
     lb_old.store(wr + A_BYTES, t);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1[i], bf1[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1[i], bf1[j], acc[i][j], 0, 0, 0);
 #pragma unroll
-    for (int g = 0; g < 4; ++g) { DISCO_SGB(SG_DS_RD, 2); DISCO_SGB(SG_MFMA, 2); }
-#pragma unroll
-    for (int g = 0; g < 4; ++g) { DISCO_SGB(SG_DS_WR, 2); DISCO_SGB(SG_MFMA, 2); }
+    for (int g = 0; g < 3; ++g) { DISCO_SGB(SG_DS_RD, 2); DISCO_SGB(SG_MFMA, 1); }
+    DISCO_SGB(SG_DS_WR, NLD / 2); DISCO_SGB(SG_MFMA, 2);
+    DISCO_SGB(SG_DS_WR, NLD - NLD / 2); DISCO_SGB(SG_MFMA, 3);
     __builtin_amdgcn_sched_barrier(0);
   };
 
@@ -192,29 +203,29 @@ constexpr int OUT_SMEM_BYTES = 128 * OUT_ROW_BYTES;       // 132 KiB
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 template <bool ACCUMULATE>
-__device__ __forceinline__ void store_tile_f32(f32x16 (&acc)[4][4], char* smem, float* out, int64_t ld, float scale) {
+__device__ __forceinline__ void store_tile_f32(f32x16 (&acc)[4][2], char* smem, float* out, int64_t ld, float scale) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = wave >> 1, wn = wave & 1, half = lane >> 5;
+  const int wm = wave >> 2, wn = wave & 3, half = lane >> 5;
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     lds_barrier();
     if (wm == h) {
 #pragma unroll
-      for (int bn = 0; bn < 4; ++bn)
+      for (int bn = 0; bn < 2; ++bn)
 #pragma unroll
         for (int bm = 0; bm < 4; ++bm)
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
             const int row = bm * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
-            const int col = wn * 128 + bn * 32 + (lane & 31);
+            const int col = wn * 64 + bn * 32 + (lane & 31);
             *reinterpret_cast<float*>(smem + row * OUT_ROW_BYTES + col * 4) = scale * acc[bm][bn][e];
           }
     }
     lds_barrier();
     const int chunk = t & 63, r0 = t >> 6;
 #pragma unroll 4
-    for (int r = 0; r < 32; ++r) {
-      const int row = r * 4 + r0;
+    for (int r = 0; r < 16; ++r) {
+      const int row = r * 8 + r0;
       f32x4 v = *reinterpret_cast<const f32x4*>(smem + row * OUT_ROW_BYTES + chunk * 16);
       float* g = out + (int64_t)(h * 128 + row) * ld + chunk * 4;
       if (ACCUMULATE) v += *reinterpret_cast<const f32x4*>(g);
