@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--path", default="auto", choices=["auto", "naive", "materialized"])
     ap.add_argument("--ranks", default="all", help="'all' (every simulated rank per step) or one rank index")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy three times (to calibrate FETCH_SIZE / WRITE_SIZE) and exit")
     return ap.parse_args()
 
 
@@ -72,6 +74,15 @@ def main():
 
     import numpy as np
     import torch
+
+    if args.copy_calibration:
+        a = torch.ones(1 << 28, dtype=torch.int32, device="cuda:0")
+        b = torch.zeros_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": a.numel() * 4, "copies": 3}))
+        return
 
     import paper_2304_08480_amd as dl
     from synth import CONFIGS, make_config_inputs

@@ -1,11 +1,24 @@
-// Device-side building blocks of the bf16 MFMA path: the 256x256x32 NT tile main loop (8 waves = two
-// per SIMD, each 128x64 = 4x2 MFMA 32x32x16 blocks, four LDS stages, swizzled 16-byte chunks), the
-// operand tile loaders and the LDS-staged tile store.  Included by mfma_kernels.hip only.
+// Device-side building blocks of the bf16 MFMA path: the 256x256x32 NT tile main loop, the operand
+// tile formats and the LDS-staged tile store.  Included by mfma_kernels.hip only.
 //
-// Why two waves per SIMD: a wave issues its instructions strictly one after the other, and an LDS write
-// or a global load keeps it busy for tens of cycles, so a lone wave cannot hide them behind its own
-// MFMAs (measured: their costs simply add up).  With a second wave on the SIMD the matrix pipe takes
-// MFMAs from one wave while the other issues memory instructions.
+// Shape of the loop.  A workgroup of 8 waves (two per SIMD) owns a 256x256 output tile; each wave owns
+// 128x64 of it as 4x2 MFMA 32x32x16 bf16 blocks with fp32 accumulators.  The reduction runs in K-steps of
+// 32 through a ring of LDS stages.  Operand tiles travel global memory -> LDS directly
+// (global_load_lds_dwordx4): no staging registers, no LDS write instructions, and the data in flight
+// lives in the ring, so a load has NSTAGE-2 K-steps to land (HBM latency under load exceeds what a
+// register-staged pipeline of this tile size can cover).  Two waves per SIMD let the matrix pipe take
+// MFMAs from one wave while the other issues LDS reads and loads.
+//
+// Operand tile formats in one LDS stage (16 KiB per operand):
+//   format K - the operand's reduction index is contiguous in memory (element (r,k) at base[r*ld + k]):
+//              256 rows of 64 bytes, 16-byte chunks swizzled so that the 16 consecutive rows a
+//              quarter-wave reads (same chunk) hit 16 different bank groups of the 64-bank LDS; fragments
+//              are read with ds_read_b128.
+//   format R - the operand's row index is contiguous in memory (element (r,k) at base[k*ld + r]): 32
+//              reduction rows of 512 bytes, 32-byte groups swizzled by the reduction row; fragments are
+//              read with the transposing ds_read_b64_tr_b16 (two per fragment).
+// A direct-to-LDS load puts lane l's 16 bytes at (wave-uniform LDS base) + 16*l, so a swizzle is applied by
+// choosing which global chunk each lane fetches.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -16,6 +29,7 @@ namespace tile {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
@@ -25,173 +39,178 @@ constexpr int NSTAGE = 4;
 constexpr int A_BYTES = BM * BK * 2;              // 16 KiB
 constexpr int STAGE_BYTES = (BM + BN) * BK * 2;   // 32 KiB
 constexpr int SMEM_BYTES = NSTAGE * STAGE_BYTES;  // 128 KiB of the CU's 160 KiB
+constexpr int LOADS_PER_STEP = 4;                 // direct-to-LDS load instructions per wave and K-step
 
-// Byte offset of 16-byte chunk `chunk` (0..3) of tile row `row` (64-byte rows: 32 bf16 of the reduction
-// index).  The LDS has 64 banks of 4 bytes, so four consecutive rows span all banks once.  Two
-// permutations keep every access pattern below conflict-free:
-//   * the chunk is XOR-ed with bits 2..3 of the row, so the 16 consecutive rows that a quarter-wave reads
-//     for an MFMA operand (same chunk) hit 16 different 16-byte bank groups;
-//   * the two low row bits are XOR-ed with bits 2..3 as well, so rows that are 4 apart (what neighbouring
-//     lanes of the transposing loader write) fall into different quarters of the banks.
-__device__ __forceinline__ uint32_t lds_off(int row, int chunk) {
-  const int g = (row >> 2) & 3;
-  return (uint32_t)(row ^ g) * 64u + (uint32_t)((chunk ^ g) << 4);
+enum { FMT_K = 0, FMT_R = 1 };
+
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+// ---- LDS reads as opaque instructions: the compiler cannot tell which direct-to-LDS load a read depends
+// on and would wait for all of them; the waits are placed by hand instead (wait_frags).
+template <int OFF>
+__device__ __forceinline__ u32x4 ds_read128(uint32_t addr) {
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ u32x2 ds_read64_tr(uint32_t addr) {
+  u32x2 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
 }
 
-// Copies a 256 x 32 bf16 operand tile from global memory to LDS through registers (512 threads).
-//   MODE 0: element (r, k) is at base[r * ld + k]   (reduction index contiguous): two 16-byte loads,
-//           thread t owns chunk t % 4 of rows t/4 and t/4 + 128;
-//   MODE 1: element (r, k) is at base[k * ld + r]   (row index contiguous): thread t loads a 4 (k) x 4 (r)
-//           block with four 8-byte loads, transposes it in registers and writes four 8-byte row pieces.
-template <int MODE>
-struct TileLoader {
-  u32x2 r[4];      // MODE 0: two 16-byte chunks as (r[0], r[1]) and (r[2], r[3]); MODE 1: four 8-byte rows
-  uint32_t voff;   // this thread's byte offset inside the tile; everything else in an address is wave-uniform
-  __device__ __forceinline__ void init(int64_t ld, int t) {
-    if (MODE == 0) voff = (uint32_t)(((t >> 2) * ld + (t & 3) * 8) * 2);
-    else voff = (uint32_t)(((t & 7) * 4 * ld + (t >> 3) * 4) * 2);
-  }
-  // base: wave-uniform pointer to element (row 0, k 0) of the tile's current K-step
-  __device__ __forceinline__ void load(const uint16_t* base, int64_t ld) {
-    if (MODE == 0) {
+// Operand fragments of one 16-wide sub-step: 4 for the A side (rows 32 i), 2 for the B side.
+struct Frags {
+  u32x4 a[4], b[2];
+};
+// All LDS reads issued so far have returned; ties the registers to the wait so no MFMA moves above it.
+__device__ __forceinline__ void wait_frags(Frags& f) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1])
+               :
+               : "memory");
+}
+
+// ---- per-lane addressing of one operand
+template <int FMT, int NFRAG>
+struct Operand {
+  uint32_t ld_off[2];       // byte offset of this lane's global chunk for the wave's two load instructions
+  uint32_t rd[NFRAG == 4 ? 4 : 2];   // FMT_K: rd[ks] base for sub-step ks; FMT_R: rd[i] base for fragment i
+  uint32_t lds_q[2];        // LDS byte offset (inside the operand tile) of the two load instructions
+
+  // row0: first tile row of this wave's fragments (multiple of 32); ld in elements
+  __device__ __forceinline__ void init(int64_t ld, int wave, int lane, int row0) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(base + (int64_t)(128 * i) * ld) + voff);
-        r[2 * i][0] = v[0]; r[2 * i][1] = v[1]; r[2 * i + 1][0] = v[2]; r[2 * i + 1][1] = v[3];
+    for (int n = 0; n < 2; ++n) {
+      const int q = 2 * wave + n;                 // which 1 KiB slice of the 16 KiB tile
+      lds_q[n] = q * 1024;
+      if (FMT == FMT_K) {
+        const int rho = 16 * q + (lane >> 2), pc = lane & 3, g = (rho >> 2) & 3;
+        ld_off[n] = (uint32_t)(((int64_t)(rho ^ g) * ld + ((pc ^ g) << 3)) * 2);
+      } else {
+        const int kap = 2 * q + (lane >> 5), pcw = lane & 31;
+        const int c = (((pcw >> 1) ^ (kap & 3)) << 1) | (pcw & 1);
+        ld_off[n] = (uint32_t)(((int64_t)kap * ld + (c << 3)) * 2);
       }
-    } else {
+    }
+    if (FMT == FMT_K) {
+      const int row = row0 + (lane & 31), g = (row >> 2) & 3, kc = lane >> 5;
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        r[e] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const char*>(base + (int64_t)e * ld) + voff);
+      for (int ks = 0; ks < 2; ++ks) rd[ks] = (uint32_t)((row ^ g) * 64 + (((ks * 2 + kc) ^ g) << 4));
+    } else {
+      const int grp = lane >> 4, L = lane & 15;
+      const int kap = (grp >> 1) * 8 + (L >> 2);  // + 16 ks + 4 h, multiples of 4: (kap & 3) unchanged
+#pragma unroll
+      for (int i = 0; i < NFRAG; ++i) {
+        const int G = (row0 + 32 * i + (grp & 1) * 16) >> 4;
+        rd[i] = (uint32_t)(kap * 512 + ((G ^ (kap & 3)) << 5) + 8 * (L & 3));
+      }
     }
   }
-  __device__ __forceinline__ void store(char* lds, int t) const {
-    if (MODE == 0) {
-      const int kb = t & 3, rb = t >> 2;
+  // issue this wave's two loads of the K-step whose tile starts at `base` into the operand tile at `lds`
+  __device__ __forceinline__ void load(const uint16_t* base, char* lds) const {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        u32x4 v;
-        v[0] = r[2 * i][0]; v[1] = r[2 * i][1]; v[2] = r[2 * i + 1][0]; v[3] = r[2 * i + 1][1];
-        *reinterpret_cast<u32x4*>(lds + lds_off(rb + 128 * i, kb)) = v;
-      }
-    } else {
-      // r[e] = (rows 0,1 | rows 2,3) of reduction index 4 kq + e.  Output row u needs reduction indices
-      // (0,1) in its first dword and (2,3) in its second: low halves for even u, high halves for odd u.
-      const int kq = t & 7, rq = t >> 3;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const uint32_t sel = (u & 1) ? 0x07060302u : 0x05040100u;
-        u32x2 o;
-        o[0] = __builtin_amdgcn_perm(r[1][u >> 1], r[0][u >> 1], sel);
-        o[1] = __builtin_amdgcn_perm(r[3][u >> 1], r[2][u >> 1], sel);
-        *reinterpret_cast<u32x2*>(lds + lds_off(rq * 4 + u, kq >> 1) + (kq & 1) * 8) = o;
-      }
+    for (int n = 0; n < 2; ++n) {
+      const char* gp = reinterpret_cast<const char*>(base) + ld_off[n];
+      char* lp = lds + __builtin_amdgcn_readfirstlane(lds_q[n]);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
+                                       (__attribute__((address_space(3))) void*)lp, 16, 0, 0);
     }
   }
 };
 
+__device__ __forceinline__ u32x4 join(u32x2 lo, u32x2 hi) { return u32x4{lo[0], lo[1], hi[0], hi[1]}; }
+
+// fragment i of sub-step KS from the operand tile at LDS byte address `tile`
+template <int FMT, int NFRAG, int KS, int I>
+__device__ __forceinline__ u32x4 read_frag(const Operand<FMT, NFRAG>& op, uint32_t tile) {
+  if (FMT == FMT_K) return ds_read128<I * 2048>(tile + op.rd[KS]);
+  return join(ds_read64_tr<KS * 8192>(tile + op.rd[I]), ds_read64_tr<KS * 8192 + 2048>(tile + op.rd[I]));
+}
+template <int FA, int FB, int KS>
+__device__ __forceinline__ void read_frags(Frags& f, const Operand<FA, 4>& a, const Operand<FB, 2>& b, uint32_t stage) {
+  f.a[0] = read_frag<FA, 4, KS, 0>(a, stage);
+  f.b[0] = read_frag<FB, 2, KS, 0>(b, stage + A_BYTES);
+  f.a[1] = read_frag<FA, 4, KS, 1>(a, stage);
+  f.b[1] = read_frag<FB, 2, KS, 1>(b, stage + A_BYTES);
+  f.a[2] = read_frag<FA, 4, KS, 2>(a, stage);
+  f.a[3] = read_frag<FA, 4, KS, 3>(a, stage);
+}
+__device__ __forceinline__ void mfma_block(const Frags& f, f32x16 (&acc)[4][2]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[i]), __builtin_bit_cast(bf16x8, f.b[j]),
+                                                          acc[i][j], 0, 0, 0);
+}
+
 // acc[bm][bn] += A_tile(256 x K) * B_tile(256 x K)^T for this wave's 128 x 64 piece.
-// A, Bp point at element (row 0, k 0) of the tile; ktiles = K / 32, which must be even and positive.
+//   FA / FB : tile format of the A / B operand (FMT_K: element (r,k) at base[r*ld + k]; FMT_R: at base[k*ld + r]).
+//   A, Bp   : element (row 0, k 0) of the workgroup's operand tiles; ktiles = K / 32 >= 1.
+//   smem    : SMEM_BYTES of LDS, 16-byte aligned; on return no load is in flight and every wave has passed
+//             a barrier, so the caller may reuse it at once.
 //
-// Software pipeline.  Four LDS stages of one 32-wide K-step each and two register sets:
-//   step kt, sub-step 0: MFMAs on the first 16 of the reduction index; fetch the fragments of sub-step 1;
-//                        issue the global loads of K-step kt+3 into the register set that is free;
-//   barrier (LDS traffic only, never the global loads);
-//   step kt, sub-step 1: MFMAs; fetch the first fragments of step kt+1 from its stage; write the other
-//                        register set (K-step kt+2, loaded during step kt-1) into stage (kt+2) % 4.
-// A global load has one and a half steps to land; an LDS stage is complete a full step before it is read
-// and is not overwritten until two barriers after its last reader.  Loads past the end are clamped to
-// the last K-step (redundant, never out of range).
-#define DISCO_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
-constexpr int SG_MFMA = 0x008, SG_VMEM_RD = 0x020, SG_DS_RD = 0x100, SG_DS_WR = 0x200;
-
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-template <int MA, int MB>
+// Pipeline: the loads of K-step kt+NSTAGE-1 are issued in step kt (after its barrier) into the stage that
+// step kt-1 used; one barrier per step, placed between the two 16-wide sub-steps:
+//   sub-step 0: MFMAs on fragments fetched during the previous step; fetch the fragments of sub-step 1;
+//   wait for this wave's loads of K-step kt+1 (vmcnt), barrier: every wave's part of that stage is in LDS
+//               and nobody reads stage (kt-1) % NSTAGE any more;
+//   sub-step 1: issue the loads of K-step kt+NSTAGE-1, fetch the first fragments of step kt+1, MFMAs.
+// Loads past the end are clamped to the last K-step (redundant, never out of range, and they keep the
+// vmcnt arithmetic uniform).
+template <int FA, int FB>
 __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bp,
                                          int64_t ldb, int ktiles, char* smem, f32x16 (&acc)[4][2]) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int64_t stepA = MA == 0 ? BK : (int64_t)BK * lda;
-  const int64_t stepB = MB == 0 ? BK : (int64_t)BK * ldb;
+  const int64_t stepA = FA == FMT_K ? BK : (int64_t)BK * lda;
+  const int64_t stepB = FB == FMT_K ? BK : (int64_t)BK * ldb;
   const int last = ktiles - 1;
-  const int arow = (wave >> 2) * 128 + (lane & 31), brow = (wave & 3) * 64 + (lane & 31), kc = lane >> 5;
-  constexpr int NLD = (MA == 0 ? 2 : 4) + (MB == 0 ? 2 : 4);   // global loads / LDS writes per thread and K-step
-  TileLoader<MA> la0, la1;
-  TileLoader<MB> lb0, lb1;
-  la0.init(lda, t); la1.init(lda, t); lb0.init(ldb, t); lb1.init(ldb, t);
-  bf16x8 af0[4], bf0[2], af1[4], bf1[2];
+  Operand<FA, 4> oa;
+  Operand<FB, 2> ob;
+  oa.init(lda, wave, lane, (wave >> 2) * 128);
+  ob.init(ldb, wave, lane, (wave & 3) * 64);
+  const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;   // LDS byte address
 
-  // prologue: K-steps 0 and 1 into stages 0 and 1, K-step 2 into register set 1
-  la0.load(A, lda);
-  lb0.load(Bp, ldb);
-  {
-    const int k1 = last < 1 ? last : 1;
-    la1.load(A + k1 * stepA, lda);
-    lb1.load(Bp + k1 * stepB, ldb);
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s) {
+    const int k = s < last ? s : last;
+    oa.load(A + k * stepA, smem + s * STAGE_BYTES);
+    ob.load(Bp + k * stepB, smem + s * STAGE_BYTES + A_BYTES);
   }
-  la0.store(smem, t);
-  lb0.store(smem + A_BYTES, t);
-  la1.store(smem + STAGE_BYTES, t);
-  lb1.store(smem + STAGE_BYTES + A_BYTES, t);
-  {
-    const int k2 = last < 2 ? last : 2;
-    la1.load(A + k2 * stepA, lda);
-    lb1.load(Bp + k2 * stepB, ldb);
-  }
+  wait_vmcnt<LOADS_PER_STEP*(NSTAGE - 2)>();
   lds_barrier();
-#pragma unroll
-  for (int i = 0; i < 4; ++i) af0[i] = *reinterpret_cast<const bf16x8*>(smem + lds_off(arow + 32 * i, kc));
-#pragma unroll
-  for (int i = 0; i < 2; ++i) bf0[i] = *reinterpret_cast<const bf16x8*>(smem + A_BYTES + lds_off(brow + 32 * i, kc));
+  Frags f0, f1;
+  read_frags<FA, FB, 0>(f0, oa, ob, smem_addr);
+  wait_frags(f0);
 
-  // one K-step: loads go into (la_new, lb_new), LDS writes come from (la_old, lb_old)
-  auto step = [&](int kt, TileLoader<MA>& la_new, TileLoader<MB>& lb_new, const TileLoader<MA>& la_old,
-                  const TileLoader<MB>& lb_old) __attribute__((always_inline)) {
-    const char* cur = smem + (kt & 3) * STAGE_BYTES;
-    const char* nxt = smem + ((kt + 1) & 3) * STAGE_BYTES;
-    char* wr = smem + ((kt + 2) & 3) * STAGE_BYTES;
-    const int kload = kt + 3 < ktiles ? kt + 3 : last;
+  for (int kt = 0; kt < ktiles; ++kt) {
+    const uint32_t cur = smem_addr + (uint32_t)((kt % NSTAGE) * STAGE_BYTES);
+    const int sn = (kt + 1) % NSTAGE, sw = (kt + NSTAGE - 1) % NSTAGE;
+    const int kload = kt + NSTAGE - 1 < ktiles ? kt + NSTAGE - 1 : last;
     // sub-step 0
-#pragma unroll
-    for (int i = 0; i < 4; ++i) af1[i] = *reinterpret_cast<const bf16x8*>(cur + lds_off(arow + 32 * i, 2 + kc));
-#pragma unroll
-    for (int i = 0; i < 2; ++i) bf1[i] = *reinterpret_cast<const bf16x8*>(cur + A_BYTES + lds_off(brow + 32 * i, 2 + kc));
-    la_new.load(A + kload * stepA, lda);
-    lb_new.load(Bp + kload * stepB, ldb);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af0[i], bf0[j], acc[i][j], 0, 0, 0);
-#pragma unroll
-    for (int g = 0; g < 3; ++g) { DISCO_SGB(SG_DS_RD, 2); DISCO_SGB(SG_MFMA, 1); }
-    DISCO_SGB(SG_VMEM_RD, NLD / 2); DISCO_SGB(SG_MFMA, 2);
-    DISCO_SGB(SG_VMEM_RD, NLD - NLD / 2); DISCO_SGB(SG_MFMA, 3);
-    __builtin_amdgcn_sched_barrier(0);   // nothing moves between sub-steps
+    read_frags<FA, FB, 1>(f1, oa, ob, cur);
+    mfma_block(f0, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt<LOADS_PER_STEP*(NSTAGE - 3)>();
+    wait_frags(f1);
+    asm volatile("s_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
     // sub-step 1
-    lds_barrier();
+    oa.load(A + kload * stepA, smem + sw * STAGE_BYTES);
+    ob.load(Bp + kload * stepB, smem + sw * STAGE_BYTES + A_BYTES);
+    read_frags<FA, FB, 0>(f0, oa, ob, smem_addr + (uint32_t)(sn * STAGE_BYTES));
+    mfma_block(f1, acc);
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) af0[i] = *reinterpret_cast<const bf16x8*>(nxt + lds_off(arow + 32 * i, kc));
-#pragma unroll
-    for (int i = 0; i < 2; ++i) bf0[i] = *reinterpret_cast<const bf16x8*>(nxt + A_BYTES + lds_off(brow + 32 * i, kc));
-    la_old.store(wr, t);
-    lb_old.store(wr + A_BYTES, t);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1[i], bf1[j], acc[i][j], 0, 0, 0);
-#pragma unroll
-    for (int g = 0; g < 3; ++g) { DISCO_SGB(SG_DS_RD, 2); DISCO_SGB(SG_MFMA, 1); }
-    DISCO_SGB(SG_DS_WR, NLD / 2); DISCO_SGB(SG_MFMA, 2);
-    DISCO_SGB(SG_DS_WR, NLD - NLD / 2); DISCO_SGB(SG_MFMA, 3);
+    wait_frags(f0);
     __builtin_amdgcn_sched_barrier(0);
-  };
-
-  // ktiles is even (callers guarantee K % 64 == 0): the two register sets alternate without a branch
-  for (int kt = 0; kt < ktiles; kt += 2) {
-    step(kt, la0, lb0, la1, lb1);
-    step(kt + 1, la1, lb1, la0, lb0);
   }
+  wait_vmcnt<0>();
+  lds_barrier();
 }
 
 // Writes a workgroup's 256 x 256 fp32 accumulator tile to row-major global memory through LDS, so that
@@ -200,7 +219,6 @@ __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A, int64_t
 // write land on different banks.  out points at the tile's first element; value = scale * acc (+ old).
 constexpr int OUT_ROW_BYTES = BN * 4 + 32;
 constexpr int OUT_SMEM_BYTES = 128 * OUT_ROW_BYTES;       // 132 KiB
-typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 template <bool ACCUMULATE>
 __device__ __forceinline__ void store_tile_f32(f32x16 (&acc)[4][2], char* smem, float* out, int64_t ld, float scale) {
