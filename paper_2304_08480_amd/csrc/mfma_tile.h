@@ -1,22 +1,26 @@
-// Device-side building blocks of the bf16 MFMA path: the 256x256x32 NT tile main loop, the operand
+// Device-side building blocks of the bf16 MFMA path: the 256x256x64 NT tile main loop, the operand
 // tile formats and the LDS-staged tile store.  Included by mfma_kernels.hip only.
 //
 // Shape of the loop.  A workgroup of 8 waves (two per SIMD) owns a 256x256 output tile; each wave owns
 // 128x64 of it as 4x2 MFMA 32x32x16 bf16 blocks with fp32 accumulators.  The reduction runs in K-steps of
-// 32 through a ring of LDS stages.  Operand tiles travel global memory -> LDS directly
+// 64 through two LDS slots.  Operand tiles travel global memory -> LDS directly
 // (global_load_lds_dwordx4): no staging registers, no LDS write instructions, and the data in flight
-// lives in the ring, so a load has NSTAGE-2 K-steps to land (HBM latency under load exceeds what a
+// lives in LDS, so a load has a whole K-step of MFMAs to land (HBM latency under load exceeds what a
 // register-staged pipeline of this tile size can cover).  Two waves per SIMD let the matrix pipe take
-// MFMAs from one wave while the other issues LDS reads and loads.
+// MFMAs from one wave while the other issues LDS reads and loads.  K-steps are 64 wide so that a load
+// instruction of a reduction-contiguous operand covers 8 rows x 128 bytes, i.e. whole cache lines
+// (with 32-wide steps each line is fetched in two halves and such loads cost twice as much).
 //
-// Operand tile formats in one LDS stage (16 KiB per operand):
+// Operand tile formats in one LDS slot (32 KiB per operand):
 //   format K - the operand's reduction index is contiguous in memory (element (r,k) at base[r*ld + k]):
-//              256 rows of 64 bytes, 16-byte chunks swizzled so that the 16 consecutive rows a
-//              quarter-wave reads (same chunk) hit 16 different bank groups of the 64-bank LDS; fragments
-//              are read with ds_read_b128.
-//   format R - the operand's row index is contiguous in memory (element (r,k) at base[k*ld + r]): 32
-//              reduction rows of 512 bytes, 32-byte groups swizzled by the reduction row; fragments are
-//              read with the transposing ds_read_b64_tr_b16 (two per fragment).
+//              256 rows of 128 bytes, 16-byte chunks XOR-swizzled with bits 1..3 of the row so that the
+//              16 consecutive rows a quarter-wave reads (same chunk) hit 16 different bank groups of the
+//              64-bank LDS; fragments are read with ds_read_b128.
+//   format R - the operand's row index is contiguous in memory (element (r,k) at base[k*ld + r]): 64
+//              reduction rows of 512 bytes; the 32-byte group index is XOR-ed with twice the low two bits
+//              of the reduction row, so the 4 reduction rows x 2 row groups that a half-wave reads at once
+//              cover a 256-byte bank window exactly; fragments are read with the transposing
+//              ds_read_b64_tr_b16 (two per fragment).
 // A direct-to-LDS load puts lane l's 16 bytes at (wave-uniform LDS base) + 16*l, so a swizzle is applied by
 // choosing which global chunk each lane fetches.
 #pragma once
@@ -34,12 +38,11 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int NTHREADS = 512;                     // 8 waves: 2 (M) x 4 (N), wave tile 128 x 64
-constexpr int BM = 256, BN = 256, BK = 32;
-constexpr int NSTAGE = 4;
-constexpr int A_BYTES = BM * BK * 2;              // 16 KiB
-constexpr int STAGE_BYTES = (BM + BN) * BK * 2;   // 32 KiB
-constexpr int SMEM_BYTES = NSTAGE * STAGE_BYTES;  // 128 KiB of the CU's 160 KiB
-constexpr int LOADS_PER_STEP = 4;                 // direct-to-LDS load instructions per wave and K-step
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int A_BYTES = BM * BK * 2;              // 32 KiB
+constexpr int STAGE_BYTES = (BM + BN) * BK * 2;   // 64 KiB
+constexpr int SMEM_BYTES = 2 * STAGE_BYTES;       // 128 KiB of the CU's 160 KiB
+constexpr int NLD = 4;                            // load instructions per wave, operand and K-step
 
 enum { FMT_K = 0, FMT_R = 1 };
 
@@ -78,47 +81,47 @@ __device__ __forceinline__ void wait_frags(Frags& f) {
 // ---- per-lane addressing of one operand
 template <int FMT, int NFRAG>
 struct Operand {
-  uint32_t ld_off[2];       // byte offset of this lane's global chunk for the wave's two load instructions
-  uint32_t rd[NFRAG == 4 ? 4 : 2];   // FMT_K: rd[ks] base for sub-step ks; FMT_R: rd[i] base for fragment i
-  uint32_t lds_q[2];        // LDS byte offset (inside the operand tile) of the two load instructions
+  uint32_t ld_off[NLD];     // byte offset of this lane's global chunk for the wave's load instructions
+  uint32_t rd[4];           // FMT_K: rd[ks] base for sub-step ks; FMT_R: rd[i] base for fragment i
+  uint32_t lds_q;           // LDS byte offset (inside the operand tile) of the wave's first load instruction
 
   // row0: first tile row of this wave's fragments (multiple of 32); ld in elements
   __device__ __forceinline__ void init(int64_t ld, int wave, int lane, int row0) {
+    lds_q = NLD * wave * 1024;
 #pragma unroll
-    for (int n = 0; n < 2; ++n) {
-      const int q = 2 * wave + n;                 // which 1 KiB slice of the 16 KiB tile
-      lds_q[n] = q * 1024;
+    for (int n = 0; n < NLD; ++n) {
+      const int q = NLD * wave + n;               // which 1 KiB slice of the 32 KiB tile
       if (FMT == FMT_K) {
-        const int rho = 16 * q + (lane >> 2), pc = lane & 3, g = (rho >> 2) & 3;
-        ld_off[n] = (uint32_t)(((int64_t)(rho ^ g) * ld + ((pc ^ g) << 3)) * 2);
+        const int rho = 8 * q + (lane >> 3), pc = lane & 7;
+        ld_off[n] = (uint32_t)(((int64_t)rho * ld + ((pc ^ ((rho >> 1) & 7)) << 3)) * 2);
       } else {
         const int kap = 2 * q + (lane >> 5), pcw = lane & 31;
-        const int c = (((pcw >> 1) ^ (kap & 3)) << 1) | (pcw & 1);
+        const int c = (((pcw >> 1) ^ ((kap & 3) << 1)) << 1) | (pcw & 1);
         ld_off[n] = (uint32_t)(((int64_t)kap * ld + (c << 3)) * 2);
       }
     }
     if (FMT == FMT_K) {
-      const int row = row0 + (lane & 31), g = (row >> 2) & 3, kc = lane >> 5;
+      const int row = row0 + (lane & 31), g = (row >> 1) & 7, kc = lane >> 5;
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) rd[ks] = (uint32_t)((row ^ g) * 64 + (((ks * 2 + kc) ^ g) << 4));
+      for (int ks = 0; ks < 4; ++ks) rd[ks] = (uint32_t)(row * 128 + (((ks * 2 + kc) ^ g) << 4));
     } else {
       const int grp = lane >> 4, L = lane & 15;
       const int kap = (grp >> 1) * 8 + (L >> 2);  // + 16 ks + 4 h, multiples of 4: (kap & 3) unchanged
 #pragma unroll
       for (int i = 0; i < NFRAG; ++i) {
         const int G = (row0 + 32 * i + (grp & 1) * 16) >> 4;
-        rd[i] = (uint32_t)(kap * 512 + ((G ^ (kap & 3)) << 5) + 8 * (L & 3));
+        rd[i] = (uint32_t)(kap * 512 + ((G ^ ((kap & 3) << 1)) << 5) + 8 * (L & 3));
       }
     }
   }
-  // issue this wave's two loads of the K-step whose tile starts at `base` into the operand tile at `lds`
+  // issue this wave's loads of the K-step whose tile starts at `base` into the operand tile at `lds`
   __device__ __forceinline__ void load(const uint16_t* base, char* lds) const {
+    char* l0 = lds + __builtin_amdgcn_readfirstlane(lds_q);
 #pragma unroll
-    for (int n = 0; n < 2; ++n) {
+    for (int n = 0; n < NLD; ++n) {
       const char* gp = reinterpret_cast<const char*>(base) + ld_off[n];
-      char* lp = lds + __builtin_amdgcn_readfirstlane(lds_q[n]);
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
-                                       (__attribute__((address_space(3))) void*)lp, 16, 0, 0);
+                                       (__attribute__((address_space(3))) void*)(l0 + n * 1024), 16, 0, 0);
     }
   }
 };
@@ -128,7 +131,7 @@ __device__ __forceinline__ u32x4 join(u32x2 lo, u32x2 hi) { return u32x4{lo[0], 
 // fragment i of sub-step KS from the operand tile at LDS byte address `tile`
 template <int FMT, int NFRAG, int KS, int I>
 __device__ __forceinline__ u32x4 read_frag(const Operand<FMT, NFRAG>& op, uint32_t tile) {
-  if (FMT == FMT_K) return ds_read128<I * 2048>(tile + op.rd[KS]);
+  if (FMT == FMT_K) return ds_read128<I * 4096>(tile + op.rd[KS]);
   return join(ds_read64_tr<KS * 8192>(tile + op.rd[I]), ds_read64_tr<KS * 8192 + 2048>(tile + op.rd[I]));
 }
 template <int FA, int FB, int KS>
@@ -151,18 +154,18 @@ __device__ __forceinline__ void mfma_block(const Frags& f, f32x16 (&acc)[4][2]) 
 
 // acc[bm][bn] += A_tile(256 x K) * B_tile(256 x K)^T for this wave's 128 x 64 piece.
 //   FA / FB : tile format of the A / B operand (FMT_K: element (r,k) at base[r*ld + k]; FMT_R: at base[k*ld + r]).
-//   A, Bp   : element (row 0, k 0) of the workgroup's operand tiles; ktiles = K / 32 >= 1.
+//   A, Bp   : element (row 0, k 0) of the workgroup's operand tiles; ktiles = K / 64 >= 1.
 //   smem    : SMEM_BYTES of LDS, 16-byte aligned; on return no load is in flight and every wave has passed
 //             a barrier, so the caller may reuse it at once.
 //
-// Pipeline: the loads of K-step kt+NSTAGE-1 are issued in step kt (after its barrier) into the stage that
-// step kt-1 used; one barrier per step, placed between the two 16-wide sub-steps:
-//   sub-step 0: MFMAs on fragments fetched during the previous step; fetch the fragments of sub-step 1;
-//   wait for this wave's loads of K-step kt+1 (vmcnt), barrier: every wave's part of that stage is in LDS
-//               and nobody reads stage (kt-1) % NSTAGE any more;
-//   sub-step 1: issue the loads of K-step kt+NSTAGE-1, fetch the first fragments of step kt+1, MFMAs.
-// Loads past the end are clamped to the last K-step (redundant, never out of range, and they keep the
-// vmcnt arithmetic uniform).
+// Pipeline over two LDS slots; step kt computes from slot kt & 1 in four 16-wide sub-steps, each fetching
+// the next sub-step's fragments while its MFMAs run:
+//   sub-steps 0..2;
+//   wait for this wave's loads of K-step kt+1 (vmcnt 0) and its own LDS reads, barrier: K-step kt+1 is
+//       complete in the other slot and nobody reads this slot any more (the last fragments are in registers);
+//   sub-step 3: issue the loads of K-step kt+2 into this slot, fetch the first fragments of step kt+1.
+// A load therefore has four sub-steps (one K-step of MFMAs) to land.  Loads past the end are clamped to
+// the last K-step (redundant, never out of range).
 template <int FA, int FB>
 __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bp,
                                          int64_t ldb, int ktiles, char* smem, f32x16 (&acc)[4][2]) {
@@ -176,34 +179,46 @@ __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A, int64_t
   ob.init(ldb, wave, lane, (wave & 3) * 64);
   const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;   // LDS byte address
 
-#pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s) {
-    const int k = s < last ? s : last;
-    oa.load(A + k * stepA, smem + s * STAGE_BYTES);
-    ob.load(Bp + k * stepB, smem + s * STAGE_BYTES + A_BYTES);
+  oa.load(A, smem);
+  ob.load(Bp, smem + A_BYTES);
+  {
+    const int k1 = last < 1 ? last : 1;
+    oa.load(A + k1 * stepA, smem + STAGE_BYTES);
+    ob.load(Bp + k1 * stepB, smem + STAGE_BYTES + A_BYTES);
   }
-  wait_vmcnt<LOADS_PER_STEP*(NSTAGE - 2)>();
+  wait_vmcnt<2 * NLD>();
   lds_barrier();
   Frags f0, f1;
   read_frags<FA, FB, 0>(f0, oa, ob, smem_addr);
   wait_frags(f0);
 
   for (int kt = 0; kt < ktiles; ++kt) {
-    const uint32_t cur = smem_addr + (uint32_t)((kt % NSTAGE) * STAGE_BYTES);
-    const int sn = (kt + 1) % NSTAGE, sw = (kt + NSTAGE - 1) % NSTAGE;
-    const int kload = kt + NSTAGE - 1 < ktiles ? kt + NSTAGE - 1 : last;
+    const int slot = kt & 1;
+    const uint32_t cur = smem_addr + (uint32_t)(slot * STAGE_BYTES);
+    const uint32_t nxt = smem_addr + (uint32_t)((slot ^ 1) * STAGE_BYTES);
+    const int kload = kt + 2 < ktiles ? kt + 2 : last;
     // sub-step 0
     read_frags<FA, FB, 1>(f1, oa, ob, cur);
     mfma_block(f0, acc);
     __builtin_amdgcn_sched_barrier(0);
-    wait_vmcnt<LOADS_PER_STEP*(NSTAGE - 3)>();
+    wait_frags(f1);
+    // sub-step 1
+    read_frags<FA, FB, 2>(f0, oa, ob, cur);
+    mfma_block(f1, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_frags(f0);
+    // sub-step 2
+    read_frags<FA, FB, 3>(f1, oa, ob, cur);
+    mfma_block(f0, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt<0>();
     wait_frags(f1);
     asm volatile("s_barrier" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
-    // sub-step 1
-    oa.load(A + kload * stepA, smem + sw * STAGE_BYTES);
-    ob.load(Bp + kload * stepB, smem + sw * STAGE_BYTES + A_BYTES);
-    read_frags<FA, FB, 0>(f0, oa, ob, smem_addr + (uint32_t)(sn * STAGE_BYTES));
+    // sub-step 3
+    oa.load(A + kload * stepA, smem + slot * STAGE_BYTES);
+    ob.load(Bp + kload * stepB, smem + slot * STAGE_BYTES + A_BYTES);
+    read_frags<FA, FB, 0>(f0, oa, ob, nxt);
     mfma_block(f1, acc);
     __builtin_amdgcn_sched_barrier(0);
     wait_frags(f0);
