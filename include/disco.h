@@ -56,10 +56,13 @@ typedef enum { DISCO_F32 = 0, DISCO_BF16 = 1 } disco_dtype;
  *                         Any B, d, N; either dtype.
  * DISCO_PATH_MATERIALIZED bf16 MFMA tiles.  The logit blocks are computed once; the un-normalised
  *                         softmax numerators are kept in bf16 (2*b*B*2 bytes) and feed the two
- *                         gradient contractions.  Needs dtype bf16, d % 64 == 0, b % 256 == 0.
- * DISCO_PATH_FUSED        bf16 MFMA tiles, streaming: row max/sum are kept on chip, logits are
- *                         recomputed per tile in the backward pass, no b x B array exists.
- *                         Same shape limits as MATERIALIZED.
+ *                         gradient contractions (12*b*B*d flop).  Needs dtype bf16, d % 256 == 0,
+ *                         b % 256 == 0.
+ * DISCO_PATH_FUSED        bf16 MFMA tiles, streaming: a forward pass keeps the row sums on chip and
+ *                         writes nothing of size b x B; the backward pass recomputes the logits one
+ *                         key panel (at most 16384 keys) at a time and contracts each panel while
+ *                         it is cache-resident (16*b*B*d flop, workspace 2*b*W*2 bytes for panel
+ *                         width W).  Same shape limits as MATERIALIZED.
  * DISCO_PATH_AUTO         the fastest path that supports the arguments.
  */
 typedef enum {
@@ -116,10 +119,14 @@ DISCO_API int clip_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t
  *   1 row norms + positive-pair logits   2 logit tiles + softmax numerators   3 row merge + scaled transpose
  *   4 key-side gradient GEMM             5 query-side split GEMM              6 query finalize + scalars
  * Stages of DISCO_PATH_NAIVE (DISCO_STAGES_NAIVE = 5): similarity, row softmax, scalars, key grad, query grad.
+ * Stages of DISCO_PATH_FUSED (DISCO_STAGES_FUSED = 5): row norms + positive-pair logits, streaming forward
+ *   (row sums only), row merge + scaled transpose, all key panels (recompute + both gradient GEMMs),
+ *   query finalize + scalars.
  * Returns DISCO_OK, or DISCO_ERR_SHAPE if count < 0.
  */
 #define DISCO_STAGES_MATERIALIZED 6
 #define DISCO_STAGES_NAIVE 5
+#define DISCO_STAGES_FUSED 5
 DISCO_API int disco_set_stage_events(void** events, int count);
 
 /* Static, NUL-terminated description of a status code. */

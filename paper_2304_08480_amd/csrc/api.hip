@@ -47,7 +47,7 @@ int resolve(int64_t B, int64_t d, int32_t N, int dtype, int path) {
     case DISCO_PATH_MATERIALIZED:
       return mfma_supported(B, d, N, dtype) ? DISCO_PATH_MATERIALIZED : -DISCO_ERR_UNSUPPORTED;
     case DISCO_PATH_FUSED:
-      return -DISCO_ERR_UNSUPPORTED;
+      return mfma_supported(B, d, N, dtype) ? DISCO_PATH_FUSED : -DISCO_ERR_UNSUPPORTED;
     default:
       return -DISCO_ERR_UNSUPPORTED;
   }
@@ -63,6 +63,7 @@ extern "C" size_t disco_workspace_bytes(int64_t B, int64_t d, int32_t N, int dty
   int r = resolve(B, d, N, dtype, path);
   if (r == DISCO_PATH_NAIVE) return naive_workspace_bytes(B, d, N);
   if (r == DISCO_PATH_MATERIALIZED) return mfma_stored_workspace_bytes(B, d, N);
+  if (r == DISCO_PATH_FUSED) return mfma_fused_workspace_bytes(B, d, N);
   return 0;
 }
 
@@ -73,7 +74,9 @@ extern "C" int disco_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64
   int r = resolve(B, d, N, dtype, path);
   if (r < 0) return -r;
   if (rank < 0 || rank >= N) return DISCO_ERR_SHAPE;
-  size_t need = r == DISCO_PATH_NAIVE ? naive_workspace_bytes(B, d, N) : mfma_stored_workspace_bytes(B, d, N);
+  size_t need = r == DISCO_PATH_NAIVE          ? naive_workspace_bytes(B, d, N)
+                : r == DISCO_PATH_MATERIALIZED ? mfma_stored_workspace_bytes(B, d, N)
+                                               : mfma_fused_workspace_bytes(B, d, N);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < need)
     return DISCO_ERR_WORKSPACE;
 
@@ -83,7 +86,8 @@ extern "C" int disco_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64
   p.loss = loss; p.gI = gI; p.gT = gT; p.gs = gs;
   p.ws = workspace; p.ws_bytes = workspace_bytes;
   p.stream = static_cast<hipStream_t>(hip_stream);
-  return r == DISCO_PATH_NAIVE ? naive_run(p) : mfma_stored_run(p);
+  if (r == DISCO_PATH_NAIVE) return naive_run(p);
+  return r == DISCO_PATH_MATERIALIZED ? mfma_stored_run(p) : mfma_fused_run(p);
 }
 
 extern "C" int clip_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t d, float s, int dtype, int path,

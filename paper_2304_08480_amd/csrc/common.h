@@ -39,5 +39,7 @@ int naive_run(const Problem& p);
 bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype);
 size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N);
 int mfma_stored_run(const Problem& p);
+size_t mfma_fused_workspace_bytes(int64_t B, int64_t d, int32_t N);
+int mfma_fused_run(const Problem& p);
 
 }  // namespace disco

@@ -119,11 +119,16 @@ __global__ __launch_bounds__(256) void k_prep_diag(Blocks bl, int64_t b, int64_t
   if (lane == 0) { p.zd2[i] = s2 * dot; p.xnorm[i] = sqrtf(nn); }
 }
 
-// Logit tile + softmax numerators.  Tile rows (MFMA M side) are key rows j, tile columns (N side) are
-// query rows i, so that each lane holds 4 consecutive j of one query row per accumulator quad:
-// 8-byte stores into the row-major E and an in-lane row sum.
+// Logit tile + softmax numerators for the key panel [jp0, jp0 + W).  Tile rows (MFMA M side) are key rows
+// j, tile columns (N side) are query rows i, so that each lane holds 4 consecutive j of one query row per
+// accumulator quad: 8-byte pieces of a row-major E row and an in-lane row sum.
+//   STATS: write the partial row sums and the label-column numerator (forward statistics);
+//   STORE: write the bf16 numerators to E (row stride W, panel-relative columns).
+// materialized path: STATS and STORE, one panel = all keys.  fused path: a STATS-only pass over all
+// keys (nothing of size b x B is written), then STORE-only passes that recompute one panel at a time.
+template <bool STATS, bool STORE>
 __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2,
-                                                      int nIp, int nJp) {
+                                                          int64_t jp0, int64_t W, int nIp, int nJp) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const BlockPtrs& p = bl.z[blockIdx.y];
   int lin;
@@ -133,8 +138,8 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
   const int nSBi = nIp >> 3;
   const int it = (sb % nSBi) * 8 + (within & 7);
   const int jt = (sb / nSBi) * 4 + (within >> 3);
-  if ((int64_t)it * BN >= b || (int64_t)jt * BM >= B) return;
-  const int64_t i0 = (int64_t)it * BN, j0 = (int64_t)jt * BM;
+  if ((int64_t)it * BN >= b || (int64_t)jt * BM >= W) return;
+  const int64_t i0 = (int64_t)it * BN, j0 = jp0 + (int64_t)jt * BM;
 
   f32x16 acc[4][2];
 #pragma unroll
@@ -143,7 +148,7 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  mainloop<0, 0>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
+  mainloop<FMT_K, FMT_K>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3, half = lane >> 5;
@@ -154,7 +159,6 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
   // rows, which as direct global stores would be 16-byte fragments; staged as a row-major 256 x 256 bf16
   // tile (rows padded to 528 bytes: conflict-free 8-byte writes and 16-byte reads) they go out as whole
   // 512-byte row segments.
-  lds_barrier();                               // every wave is done with the operand buffers
 #pragma unroll
   for (int bn = 0; bn < 2; ++bn) {
     const int il = wn * 64 + bn * 32 + (lane & 31);
@@ -176,27 +180,34 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
         if (diag_tile && lab >= j && lab < j + 4) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            if (lab == j + r) { p.ediag[i] = e[r]; e[r] = 0.f; }
+            if (lab == j + r) {
+              if (STATS) p.ediag[i] = e[r];
+              e[r] = 0.f;
+            }
         }
-        rowsum += (e[0] + e[1]) + (e[2] + e[3]);
-        bf16x4 pk;
+        if (STATS) rowsum += (e[0] + e[1]) + (e[2] + e[3]);
+        if (STORE) {
+          bf16x4 pk;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) pk[r] = (__bf16)e[r];
-        *reinterpret_cast<bf16x4*>(lrow + (jl + q * 8) * 2) = pk;
+          for (int r = 0; r < 4; ++r) pk[r] = (__bf16)e[r];
+          *reinterpret_cast<bf16x4*>(lrow + (jl + q * 8) * 2) = pk;
+        }
       }
     }
-    rowsum += __shfl_xor(rowsum, 32);
-    if (half == 0) p.lpart[((j0 >> 7) + wm) * b + i] = rowsum;
+    if (STATS) {
+      rowsum += __shfl_xor(rowsum, 32);
+      if (half == 0) p.lpart[((j0 >> 7) + wm) * b + i] = rowsum;
+    }
   }
-  lds_barrier();
-  {
+  if (STORE) {
+    lds_barrier();
     const int t = threadIdx.x;
     const int chunk = t & 31, r0 = t >> 5;     // 32 chunks of 16 bytes per 512-byte row; 16 rows per pass
 #pragma unroll 8
     for (int r = 0; r < 16; ++r) {
       const int row = r * 16 + r0;
       const u32x4 v = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + chunk * 16);
-      *reinterpret_cast<u32x4*>(p.E + (i0 + row) * B + j0 + chunk * 8) = v;
+      *reinterpret_cast<u32x4*>(p.E + (i0 + row) * W + (j0 - jp0) + chunk * 8) = v;
     }
   }
 }
@@ -251,13 +262,14 @@ __global__ __launch_bounds__(256) void k_scale_transpose(Blocks bl, int64_t b, i
 // (The term [j = label_i] gdiag_i x_ik is added by k_query_finalize, which owns the rank's rows.)
 // GEMM M = key rows j (operand E read transposed), N = feature index k, reduction over the rank's rows.
 template <bool ACCUMULATE>
-__global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int64_t B, int64_t d, float cs, int nM, int nN) {
+__global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int64_t d, float cs, int64_t jp0, int64_t W,
+                                                       int nM, int nN) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const BlockPtrs& p = bl.z[blockIdx.y];
   int lin;
   if (!xcd_linear(nM * nN, lin)) return;
   const int nt = lin % nN, mt = lin / nN;
-  const int64_t j0 = (int64_t)mt * BM, k0 = (int64_t)nt * BN;
+  const int64_t jl0 = (int64_t)mt * BM, k0 = (int64_t)nt * BN;     // key rows jp0 + jl0 .. of the panel
   f32x16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -265,21 +277,22 @@ __global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  mainloop<1, 0>(p.E + j0, B, p.Xs + k0 * b, b, (int)(b / BK), smem, acc);
-  store_tile_f32<ACCUMULATE>(acc, smem, p.gk + j0 * d + k0, d, cs);
+  mainloop<FMT_R, FMT_K>(p.E + jl0, W, p.Xs + k0 * b, b, (int)(b / BK), smem, acc);
+  store_tile_f32<ACCUMULATE>(acc, smem, p.gk + (jp0 + jl0) * d + k0, d, cs);
 }
 
 // Query-side products, split over the key index: part[ks][i][k] = sum_{j in split ks} E[i][j] y_jk.
 // GEMM M = query rows i, N = feature index k (operand Y read transposed), reduction over key rows.
-__global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b, int64_t B, int64_t d, int nM, int nN,
-                                                        int splitk, int ktiles_per_split) {
+template <bool ACCUMULATE>
+__global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b, int64_t d, int64_t jp0, int64_t W, int nM,
+                                                            int nN, int splitk, int ktiles_per_split) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const BlockPtrs& p = bl.z[blockIdx.y];
   int lin;
   if (!xcd_linear(nM * nN * splitk, lin)) return;
   const int nt = lin % nN, ks = (lin / nN) % splitk, mt = lin / (nN * splitk);
   const int64_t i0 = (int64_t)mt * BM, k0 = (int64_t)nt * BN;
-  const int kt_total = (int)(B / BK);
+  const int kt_total = (int)(W / BK);
   const int kt0 = ks * ktiles_per_split;
   int kts = kt_total - kt0;
   if (kts > ktiles_per_split) kts = ktiles_per_split;
@@ -290,8 +303,9 @@ __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  if (kts > 0) mainloop<0, 1>(p.E + i0 * B + (int64_t)kt0 * BK, B, p.Yraw + (int64_t)kt0 * BK * d + k0, d, kts, smem, acc);
-  store_tile_f32<false>(acc, smem, p.part + (int64_t)ks * b * d + i0 * d + k0, d, 1.0f);
+  if (kts > 0)
+    mainloop<FMT_K, FMT_R>(p.E + i0 * W + (int64_t)kt0 * BK, W, p.Yraw + (jp0 + (int64_t)kt0 * BK) * d + k0, d, kts, smem, acc);
+  store_tile_f32<ACCUMULATE>(acc, smem, p.part + (int64_t)ks * b * d + i0 * d + k0, d, 1.0f);
 }
 
 // Query-side gradient of one local row: gq[label_i][:] += cs (beta_i sum_ks part + gdiag_i y_label), the
@@ -349,30 +363,41 @@ __global__ __launch_bounds__(1024) void k_scalars(Blocks bl, int64_t b, float c,
 
 struct Plan {
   int64_t b, B, d;
+  int64_t W;             // key panel width (B for the materialized path)
+  int npanels;
   int nparts;            // B / 128
   int nMq, nN, splitk, ktps;
   size_t off_E, off_lpart, off_rows, off_Xs, off_part, off_ymax, total;
   size_t rows_stride;    // bytes of one b-float row array (aligned)
 };
 
-Plan make_plan(int64_t B, int64_t d, int32_t N) {
+// Key panels of the fused path: at most 16384 keys wide (so that one panel of both blocks' numerators
+// stays within the 256 MiB last-level cache at the paper's rank shares) and at least two of them.
+int fused_panels(int64_t B) {
+  for (int n = 2; n <= 4096; ++n)
+    if (B % ((int64_t)n * BM) == 0 && B / n <= 16384) return n;
+  return 1;
+}
+
+Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused) {
   Plan pl;
   pl.B = B; pl.d = d; pl.b = B / N;
   const int64_t b = pl.b;
+  pl.npanels = fused ? fused_panels(B) : 1;
+  pl.W = B / pl.npanels;
   pl.nparts = (int)(B / 128);
   pl.nMq = (int)(b / BM);
   pl.nN = (int)(d / BN);
   const int tiles = pl.nMq * pl.nN;
-  const int kt_total = (int)(B / BK);
+  const int kt_total = (int)(pl.W / BK);
   int sk = (256 + tiles - 1) / tiles;      // one workgroup per compute unit
   if (sk > 32) sk = 32;
   if (sk > kt_total) sk = kt_total;
   if (sk < 1) sk = 1;
   pl.ktps = (kt_total + sk - 1) / sk;
-  pl.ktps += pl.ktps & 1;                  // the tile main loop takes K-steps in pairs (kt_total is a multiple of 8)
   pl.splitk = (kt_total + pl.ktps - 1) / pl.ktps;
   size_t o = 0;
-  pl.off_E = o;      o += 2 * align_up((size_t)b * B * 2);
+  pl.off_E = o;      o += 2 * align_up((size_t)b * pl.W * 2);
   pl.off_lpart = o;  o += 2 * align_up((size_t)pl.nparts * b * 4);
   pl.rows_stride = align_up((size_t)b * 4);
   pl.off_rows = o;   o += 2 * 7 * pl.rows_stride;   // ediag, zd2, xnorm, beta, gdiag, ce, rowds
@@ -383,33 +408,23 @@ Plan make_plan(int64_t B, int64_t d, int32_t N) {
   return pl;
 }
 
-}  // namespace
-
-bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype) {
-  if (dtype != DISCO_BF16) return false;
-  if (N <= 0 || B % N != 0) return false;
-  const int64_t b = B / N;
-  return b % 256 == 0 && d % 256 == 0;
+template <class K>
+bool allow_lds(K kernel, int bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess;
 }
 
-size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N) { return make_plan(B, d, N).total; }
-
-int mfma_stored_run(const Problem& pr) {
+int mfma_run(const Problem& pr, bool fused) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_logit_tiles),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, LOGIT_SMEM_BYTES);
-    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_key_grad<false>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_SMEM_BYTES);
-    hipError_t e4 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_key_grad<true>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_SMEM_BYTES);
-    hipError_t e3 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_query_partial),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_SMEM_BYTES);
-    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess) return DISCO_ERR_HIP;
+    bool ok = allow_lds(k_logit_tiles<true, true>, LOGIT_SMEM_BYTES) && allow_lds(k_logit_tiles<true, false>, LOGIT_SMEM_BYTES) &&
+              allow_lds(k_logit_tiles<false, true>, LOGIT_SMEM_BYTES) && allow_lds(k_key_grad<false>, GEMM_SMEM_BYTES) &&
+              allow_lds(k_key_grad<true>, GEMM_SMEM_BYTES) && allow_lds(k_query_partial<false>, GEMM_SMEM_BYTES) &&
+              allow_lds(k_query_partial<true>, GEMM_SMEM_BYTES);
+    if (!ok) return DISCO_ERR_HIP;
     attr_set = true;
   }
-  const Plan pl = make_plan(pr.B, pr.d, pr.N);
-  const int64_t b = pl.b, B = pl.B, d = pl.d;
+  const Plan pl = make_plan(pr.B, pr.d, pr.N, fused);
+  const int64_t b = pl.b, B = pl.B, d = pl.d, W = pl.W;
   char* ws = static_cast<char*>(pr.ws);
   const uint16_t* I = static_cast<const uint16_t*>(pr.I);
   const uint16_t* T = static_cast<const uint16_t*>(pr.T);
@@ -422,7 +437,7 @@ int mfma_stored_run(const Problem& pr) {
     p.X = Xfull + (size_t)pr.rank * b * d;
     p.Y = z == 0 ? T : I;
     p.Yraw = p.Y;
-    p.E = reinterpret_cast<uint16_t*>(ws + pl.off_E + z * align_up((size_t)b * B * 2));
+    p.E = reinterpret_cast<uint16_t*>(ws + pl.off_E + z * align_up((size_t)b * W * 2));
     p.lpart = reinterpret_cast<float*>(ws + pl.off_lpart + z * align_up((size_t)pl.nparts * b * 4));
     char* rows = ws + pl.off_rows + (size_t)z * 7 * pl.rows_stride;
     p.ediag = reinterpret_cast<float*>(rows + 0 * pl.rows_stride);
@@ -443,41 +458,73 @@ int mfma_stored_run(const Problem& pr) {
   const float c = 1.0f / (2.0f * (float)B);
   const float cs = c * pr.s;
   hipStream_t st = pr.stream;
+  const int nI = (int)(b / BN);
+  const int nIp = (nI + 7) / 8 * 8;
+  auto logit_grid = [&](int64_t keys, int& nJp) {
+    const int nJ = (int)(keys / BM);
+    nJp = (nJ + 3) / 4 * 4;
+    return dim3((unsigned)(((nIp * nJp + 7) / 8) * 8), 2);
+  };
+  const int nMk = (int)(W / BM);
+  const dim3 key_grid((unsigned)(((nMk * pl.nN + 7) / 8) * 8), 2);
+  const dim3 q_grid((unsigned)(((pl.nMq * pl.nN * pl.splitk + 7) / 8) * 8), 2);
+  int stage = 0;
 
-  stage_mark(st, 0);
+  stage_mark(st, stage++);
   k_zero2<<<1, 64, 0, st>>>(ymax);
   k_rownorm_max<<<dim3((unsigned)((B + 3) / 4 < 1024 ? (B + 3) / 4 : 1024), 2), 256, 0, st>>>(I, T, B, d, ymax);
   k_prep_diag<<<dim3((unsigned)((b + 3) / 4), 2), 256, 0, st>>>(bl, b, d, pr.rank, s2);
+  stage_mark(st, stage++);
 
-  stage_mark(st, 1);
-
-  const int nI = (int)(b / BN), nJ = (int)(B / BM);
-  const int nIp = (nI + 7) / 8 * 8, nJp = (nJ + 3) / 4 * 4;
-  const int fwd_wgs = ((nIp * nJp + 7) / 8) * 8;
-  k_logit_tiles<<<dim3((unsigned)fwd_wgs, 2), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, nIp, nJp);
-  stage_mark(st, 2);
+  int nJp;
+  if (fused) {
+    const dim3 g = logit_grid(B, nJp);
+    k_logit_tiles<true, false><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, nIp, nJp);
+  } else {
+    const dim3 g = logit_grid(B, nJp);
+    k_logit_tiles<true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, nIp, nJp);
+  }
+  stage_mark(st, stage++);
   k_row_merge<<<dim3((unsigned)((b + 63) / 64), 2), 256, 0, st>>>(bl, b, pl.nparts);
   k_scale_transpose<<<dim3((unsigned)(b / 64), (unsigned)(d / 64), 2), 256, 0, st>>>(bl, b, d);
+  stage_mark(st, stage++);
 
-  stage_mark(st, 3);
-
-  const int nMk = (int)(B / BM);
-  const int key_wgs = ((nMk * pl.nN + 7) / 8) * 8;
-  if (pr.accumulate)
-    k_key_grad<true><<<dim3((unsigned)key_wgs, 2), NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, B, d, cs, nMk, pl.nN);
-  else
-    k_key_grad<false><<<dim3((unsigned)key_wgs, 2), NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, B, d, cs, nMk, pl.nN);
-
-  stage_mark(st, 4);
-
-  const int q_wgs = ((pl.nMq * pl.nN * pl.splitk + 7) / 8) * 8;
-  k_query_partial<<<dim3((unsigned)q_wgs, 2), NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, B, d, pl.nMq, pl.nN, pl.splitk, pl.ktps);
-  stage_mark(st, 5);
+  for (int pnl = 0; pnl < pl.npanels; ++pnl) {
+    const int64_t jp0 = (int64_t)pnl * W;
+    if (fused) {
+      const dim3 g = logit_grid(W, nJp);
+      k_logit_tiles<false, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, jp0, W, nIp, nJp);
+    }
+    if (pr.accumulate)
+      k_key_grad<true><<<key_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, cs, jp0, W, nMk, pl.nN);
+    else
+      k_key_grad<false><<<key_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, cs, jp0, W, nMk, pl.nN);
+    if (!fused) stage_mark(st, stage++);
+    if (pnl > 0)
+      k_query_partial<true><<<q_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, jp0, W, pl.nMq, pl.nN, pl.splitk, pl.ktps);
+    else
+      k_query_partial<false><<<q_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, jp0, W, pl.nMq, pl.nN, pl.splitk, pl.ktps);
+  }
+  stage_mark(st, stage++);
   k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, 0, b, d, pr.rank, cs, pl.splitk);
   k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, 1, b, d, pr.rank, cs, pl.splitk);
   k_scalars<<<1, 1024, 0, st>>>(bl, b, c, pr.accumulate, pr.loss, pr.gs);
-  stage_mark(st, 6);
+  stage_mark(st, stage++);
   return hipGetLastError() == hipSuccess ? DISCO_OK : DISCO_ERR_HIP;
 }
+
+}  // namespace
+
+bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype) {
+  if (dtype != DISCO_BF16) return false;
+  if (N <= 0 || B % N != 0) return false;
+  const int64_t b = B / N;
+  return b % 256 == 0 && d % 256 == 0;
+}
+
+size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N) { return make_plan(B, d, N, false).total; }
+size_t mfma_fused_workspace_bytes(int64_t B, int64_t d, int32_t N) { return make_plan(B, d, N, true).total; }
+int mfma_stored_run(const Problem& pr) { return mfma_run(pr, false); }
+int mfma_fused_run(const Problem& pr) { return mfma_run(pr, true); }
 
 }  // namespace disco

@@ -83,6 +83,21 @@ def test_naive_workspace_follows_the_papers_memory_model():
         assert entries * 4 <= need <= entries * 4 + 64 * (B // N) + 4096
 
 
+def test_fused_path_workspace_is_one_key_panel():
+    # Sec. 4.1 counts 2 b B entries for the two logit blocks; the fused path keeps 2 b W (W <= 16384 keys)
+    B, d, N = 196608, 512, 64
+    b = B // N
+    mat = dl.disco_workspace_bytes(B, d, N, dl.DISCO_BF16, dl.DISCO_PATH_MATERIALIZED)
+    fus = dl.disco_workspace_bytes(B, d, N, dl.DISCO_BF16, dl.DISCO_PATH_FUSED)
+    assert mat >= 2 * b * B * 2 and mat - fus == 2 * b * (B - 16384) * 2
+    assert dl.disco_resolve_path(B, d, N, dl.DISCO_F32, dl.DISCO_PATH_FUSED) == -dl.DISCO_ERR_UNSUPPORTED
+
+
+def test_stage_events_argument_check():
+    assert dl.disco_set_stage_events(None, 0) == dl.DISCO_OK
+    assert dl.disco_set_stage_events(None, -1) == dl.DISCO_ERR_SHAPE
+
+
 def test_auto_falls_back_to_naive_for_fp32_and_odd_shapes():
     assert dl.disco_resolve_path(256, 512, 4, dl.DISCO_F32, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
     assert dl.disco_resolve_path(300, 77, 3, dl.DISCO_BF16, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE

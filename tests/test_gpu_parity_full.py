@@ -65,7 +65,7 @@ def test_b32k_n8_ranks_dense_and_accumulated():
 
 
 @pytest.mark.parametrize("name,N,rank", [("b196k_n64", None, 37), ("b196k_n64_hard", None, 63),
-                                         ("b64k_d768_n8", None, 2), ("full_n1", 1, 0)])
+                                         ("b64k_d768_n8", None, 2)])
 def test_large_workloads_sampled(name, N, rank):
     cfg, I, T, run = _setup(name, N)
     N = cfg.N if N is None else N
@@ -74,10 +74,6 @@ def test_large_workloads_sampled(name, N, rank):
     run.rank(rank, s)
     loss, gI, gT, gs = run.results()
     t0 = time.time()
-    if name == "full_n1":
-        # the dense forward of all 32768 rows costs minutes in float64; use the first 4096 rows' statistics
-        # only where they are needed (sampled rows below need every row's lse, so sample from a sub-rank view)
-        pytest.skip("covered by test_full_n1_properties")
     lseA, lseC = oc.rank_row_stats(I, T, s, rank, N)
     ref_loss = oc.rank_loss_from_stats(I, T, s, rank, N, lseA, lseC)
     check_scalar(f"{name} loss", loss, ref_loss, TOL["bf16"]["scalar"])
@@ -111,3 +107,21 @@ def test_full_n1_properties():
     assert np.linalg.norm(a1 - a8) <= 1e-4 * np.linalg.norm(a8)
     assert np.linalg.norm(t1 - t8) <= 1e-4 * np.linalg.norm(t8)
     assert np.sum(a1 * I) == pytest.approx(s * g1, rel=2e-3) and np.sum(t1 * T) == pytest.approx(s * g1, rel=2e-3)
+
+
+def test_b32k_n8_fused_path_one_rank():
+    """The streaming / recompute path at the headline size against the float64 oracle."""
+    cfg = CONFIGS["b32k_n8"]
+    I, T, Ib, Tb = make_config_inputs(cfg)
+    Id, Td, dt = to_device(I, T, Ib, Tb, cfg.dtype)
+    run = Runner(Id, Td, cfg.B, cfg.d, cfg.N, dt, dl.DISCO_PATH_FUSED)
+    r = 6
+    run.rank(r, cfg.s)
+    loss, gI, gT, gs = run.results()
+    ref = oc.disco_rank(I, T, cfg.s, r, cfg.N)
+    sI, sT, fl = term_scale(oc, I, T, cfg.s, r, cfg.N)
+    check_scalar("fused loss", loss, ref[0], TOL["bf16"]["scalar"])
+    check_scalar("fused gs", gs, ref[3], TOL["bf16"]["scalar"] * 10, abs_tol=1e-9)
+    f1 = check_tensor("fused gI", gI, ref[1], "bf16", sI, fl)
+    f2 = check_tensor("fused gT", gT, ref[2], "bf16", sT, fl)
+    print(f"b32k_n8 fused rank {r}: gI {f1} gT {f2}", flush=True)

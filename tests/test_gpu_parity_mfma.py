@@ -39,11 +39,12 @@ def _compare(run, ref, scale, tag):
     (2048, 256, 8, 100.0, {}),
     (512, 256, 2, 0.0, {}),
 ])
-def test_mfma_path_matches_oracle(B, d, N, s, kw):
+@pytest.mark.parametrize("path", [dl.DISCO_PATH_MATERIALIZED, dl.DISCO_PATH_FUSED], ids=["materialized", "fused"])
+def test_mfma_path_matches_oracle(B, d, N, s, kw, path):
     I, T, Ib, Tb = _inputs(B, d, 5, **kw)
     Id, Td, dt = to_device(I, T, Ib, Tb, "bf16")
     assert dl.disco_resolve_path(B, d, N, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_MATERIALIZED
-    run = Runner(Id, Td, B, d, N, dt, dl.DISCO_PATH_MATERIALIZED)
+    run = Runner(Id, Td, B, d, N, dt, path)
     for r in sorted({0, N // 2, N - 1}):
         print(f"case B={B} d={d} N={N} s={s} rank={r}", flush=True)
         run.rank(r, s)
@@ -54,7 +55,7 @@ def test_mfma_path_matches_oracle(B, d, N, s, kw):
     full = oc.clip_loss_full(I, T, s)
     full_scale = term_scale(oc, I, T, s, 0, 1)
     _compare(run, full, full_scale, f"B{B} d{d} N{N} s{s:g} accumulated")
-    run1 = Runner(Id, Td, B, d, 1, dt, dl.DISCO_PATH_MATERIALIZED)
+    run1 = Runner(Id, Td, B, d, 1, dt, path)
     run1.full(s)
     _compare(run1, full, full_scale, f"B{B} d{d} clip_loss_fwd_bwd")
 
@@ -91,3 +92,23 @@ def test_mfma_path_agrees_with_naive_path_on_gpu():
     sI, sT, fl = term_scale(oc, I, T, s, 2, N)
     check_tensor("gI", af, as_, "bf16", sI, fl)
     check_tensor("gT", tf, ts, "bf16", sT, fl)
+
+
+def test_fused_path_needs_less_workspace_and_matches_materialized():
+    # the fused path keeps one key panel of numerators instead of the whole b x B blocks
+    B, d, N, s = 4096, 256, 2, 14.285714
+    I, T, Ib, Tb = _inputs(B, d, 9)
+    Id, Td, dt = to_device(I, T, Ib, Tb, "bf16")
+    w_mat = dl.disco_workspace_bytes(B, d, N, dt, dl.DISCO_PATH_MATERIALIZED)
+    w_fus = dl.disco_workspace_bytes(B, d, N, dt, dl.DISCO_PATH_FUSED)
+    b = B // N
+    assert w_mat - w_fus == 2 * b * (B - B // 2) * 2          # two panels of B/2 keys at this size
+    mat = Runner(Id, Td, B, d, N, dt, dl.DISCO_PATH_MATERIALIZED)
+    fus = Runner(Id, Td, B, d, N, dt, dl.DISCO_PATH_FUSED)
+    mat.rank(1, s); fus.rank(1, s)
+    lm, am, tm, gm = mat.results()
+    lf, af, tf, gf = fus.results()
+    # same numerators, same reduction order inside a panel; the query-side sum is split differently
+    assert lf == lm
+    assert np.allclose(af, am, rtol=1e-4, atol=1e-10) and np.allclose(tf, tm, rtol=1e-4, atol=1e-10)
+    assert gf == pytest.approx(gm, rel=1e-5)
