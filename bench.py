@@ -121,13 +121,9 @@ def main():
         step()
     torch.cuda.synchronize()
 
-    # timed region: exactly `steps` steps; stage events are recorded by the library on the same stream
-    # (the last call's events survive: one rank call of the last step)
-    dl.disco_set_stage_events(ev.arr, ev.n)
+    # timed region: exactly `steps` steps, no stage events (they cost about 2 % between kernels)
     t_start = torch.cuda.Event(enable_timing=True)
     t_end = torch.cuda.Event(enable_timing=True)
-    stage_ms = np.zeros(nstages)
-    stage_samples = 0
     torch.cuda.synchronize()
     wall0 = time.perf_counter()
     t_start.record(stream)
@@ -137,18 +133,20 @@ def main():
     torch.cuda.synchronize()
     wall1 = time.perf_counter()
     total_ms = t_start.elapsed_time(t_end)
-    # the events now hold the last rank call of the last step
-    for i in range(nstages):
-        stage_ms[i] = ev.elapsed_ms(i, i + 1)
-    stage_samples = 1
-    # a few more calls only to average the stage intervals (outside the throughput figure)
-    extra = min(20, max(4, args.steps))
+
+    # stage intervals: the same steps again with the library recording HIP events between its stages on the
+    # stream it launches on; averaged over every rank call of `stage_steps` steps
+    dl.disco_set_stage_events(ev.arr, ev.n)
+    stage_steps = min(args.steps, 3)
     acc = np.zeros(nstages)
-    for k in range(extra):
-        dl.disco_loss_fwd_bwd(Id, Td, B, d, ranks[k % len(ranks)], N, s, dt, path, 1, loss, gI, gT, gs, ws, ws_bytes, stream)
-        torch.cuda.synchronize()
-        acc += np.array([ev.elapsed_ms(i, i + 1) for i in range(nstages)])
-    stage_avg = acc / extra
+    ncalls = 0
+    for k in range(stage_steps):
+        for n, r in enumerate(ranks):
+            dl.disco_loss_fwd_bwd(Id, Td, B, d, r, N, s, dt, path, 1 if n > 0 else 0, loss, gI, gT, gs, ws, ws_bytes, stream)
+            torch.cuda.synchronize()
+            acc += np.array([ev.elapsed_ms(i, i + 1) for i in range(nstages)])
+            ncalls += 1
+    stage_avg = acc / ncalls
     dl.disco_set_stage_events(None, 0)
 
     ms_per_step = total_ms / args.steps

@@ -76,9 +76,10 @@ __global__ void k_zero2(uint32_t* p) { if (threadIdx.x < 2) p[threadIdx.x] = 0u;
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// max over all rows of |row|^2 for I (slot 0) and T (slot 1).  One wave per row at a time (16-byte
-// loads, d is a multiple of 8), grid-stride over rows, one atomicMax per workgroup (max is
-// order-independent, so the result is deterministic; values are >= 0 so the bit patterns order like floats).
+// max over all rows of |row|^2 for I (slot 0) and T (slot 1).  A wave takes 8 rows at a time (one 16-byte
+// load per lane and row in flight, d is a multiple of 8), reduces the 8 row sums with interleaved
+// butterflies, and keeps a running maximum; one atomicMax per workgroup (max is order-independent, so the
+// result is deterministic; values are >= 0 so the bit patterns order like floats).
 __global__ __launch_bounds__(256) void k_rownorm_max(const uint16_t* I, const uint16_t* T, int64_t B, int64_t d,
                                                       uint32_t* out) {
   __shared__ float red[4];
@@ -86,14 +87,31 @@ __global__ __launch_bounds__(256) void k_rownorm_max(const uint16_t* I, const ui
   const uint16_t* M = which == 0 ? I : T;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float best = 0.f;
-  for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < B; row += (int64_t)gridDim.x * 4) {
-    float a = 0.f;
-    for (int64_t k = lane * 8; k < d; k += 512) {
-      const u32x4 v = *reinterpret_cast<const u32x4*>(M + row * d + k);
+  for (int64_t row0 = ((int64_t)blockIdx.x * 4 + wave) * 8; row0 < B; row0 += (int64_t)gridDim.x * 32) {
+    float a[8];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) { a = fmaf(bf16_lo(v[q]), bf16_lo(v[q]), a); a = fmaf(bf16_hi(v[q]), bf16_hi(v[q]), a); }
+    for (int r = 0; r < 8; ++r) a[r] = 0.f;
+    for (int64_t k = lane * 8; k < d; k += 512) {
+      u32x4 v[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const int64_t row = row0 + r < B ? row0 + r : B - 1;     // clamp: a repeated row does not change the max
+        v[r] = *reinterpret_cast<const u32x4*>(M + row * d + k);
+      }
+#pragma unroll
+      for (int r = 0; r < 8; ++r)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          a[r] = fmaf(bf16_lo(v[r][q]), bf16_lo(v[r][q]), a[r]);
+          a[r] = fmaf(bf16_hi(v[r][q]), bf16_hi(v[r][q]), a[r]);
+        }
     }
-    best = fmaxf(best, wave_sum(a));
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+#pragma unroll
+      for (int r = 0; r < 8; ++r) a[r] += __shfl_xor(a[r], o);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) best = fmaxf(best, a[r]);
   }
   if (lane == 0) red[wave] = best;
   __syncthreads();
@@ -472,7 +490,7 @@ int mfma_run(const Problem& pr, bool fused) {
 
   stage_mark(st, stage++);
   k_zero2<<<1, 64, 0, st>>>(ymax);
-  k_rownorm_max<<<dim3((unsigned)((B + 3) / 4 < 1024 ? (B + 3) / 4 : 1024), 2), 256, 0, st>>>(I, T, B, d, ymax);
+  k_rownorm_max<<<dim3((unsigned)((B + 31) / 32 < 1024 ? (B + 31) / 32 : 1024), 2), 256, 0, st>>>(I, T, B, d, ymax);
   k_prep_diag<<<dim3((unsigned)((b + 3) / 4), 2), 256, 0, st>>>(bl, b, d, pr.rank, s2);
   stage_mark(st, stage++);
 
