@@ -23,6 +23,10 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3      # MI355X fp32 vector
 
+# HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs whose
+# summary is profiles/b32k_n8_hbm_traffic.txt (counters cannot be read from inside this process).
+MEASURED_TRAFFIC_BYTES = {("b32k_n8", "materialized", "logit_tiles"): 9.571e8}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -179,7 +183,8 @@ def main():
     achieved = dom_flops / (dom_ms * 1e-3) / 1e12
     roofline = {
         "bound": bound, "kernel": names[dom], "achieved": round(achieved, 2), "peak": peak, "unit": unit,
-        "frac": round(achieved / peak, 4), "traffic": None,
+        "frac": round(achieved / peak, 4),
+        "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, {1: "naive", 2: "materialized", 3: "fused"}[resolved], names[dom])),
         "avg_launch_ms": round(dom_ms, 4), "flops_per_launch": dom_flops,
         "stages_ms": {n: round(float(v), 4) for n, v in zip(names, stage_avg)},
     }
