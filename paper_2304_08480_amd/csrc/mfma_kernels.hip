@@ -15,9 +15,9 @@
 //   d/ds share           c <gX_i / (c s), x_i>  summed over i   (sum_ij G_ij S_ij = <G Y, X>)
 // Since lse_i >= z_i,label, every E_ij that underflows is negligible against the row total.
 //
-// One 256x256x32 NT tile main loop (8 waves, each 128x64 = 4x2 MFMA 32x32x16 blocks, four LDS stages,
-// swizzled 16-byte chunks) serves all three contractions; operands whose reduction index is not the
-// contiguous one in memory are transposed in registers (4x4 blocks of bf16) on their way into LDS.
+// One 256x256x64 NT tile main loop (mfma_tile.h: 8 waves, each 128x64 = 4x2 MFMA 32x32x16 blocks, operands
+// loaded global -> LDS directly into a ring of five units) serves all three contractions; operands whose
+// reduction index is not the contiguous one in memory are read from LDS with transposing loads.
 #include "common.h"
 #include "mfma_tile.h"
 
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  mainloop<FMT_K, FMT_K>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
+  mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3, half = lane >> 5;
@@ -295,7 +295,7 @@ __global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  mainloop<FMT_R, FMT_K>(p.E + jl0, W, p.Xs + k0 * b, b, (int)(b / BK), smem, acc);
+  mainloop<FMT_R, FMT_K, true>(p.E + jl0, W, p.Xs + k0 * b, b, (int)(b / BK), smem, acc);
   store_tile_f32<ACCUMULATE>(acc, smem, p.gk + (jp0 + jl0) * d + k0, d, cs);
 }
 
@@ -322,7 +322,7 @@ __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   if (kts > 0)
-    mainloop<FMT_K, FMT_R>(p.E + i0 * W + (int64_t)kt0 * BK, W, p.Yraw + (jp0 + (int64_t)kt0 * BK) * d + k0, d, kts, smem, acc);
+    mainloop<FMT_K, FMT_R, false>(p.E + i0 * W + (int64_t)kt0 * BK, W, p.Yraw + (jp0 + (int64_t)kt0 * BK) * d + k0, d, kts, smem, acc);
   store_tile_f32<ACCUMULATE>(acc, smem, p.part + (int64_t)ks * b * d + i0 * d + k0, d, 1.0f);
 }
 

@@ -3,15 +3,20 @@
 //
 // Shape of the loop.  A workgroup of 8 waves (two per SIMD) owns a 256x256 output tile; each wave owns
 // 128x64 of it as 4x2 MFMA 32x32x16 bf16 blocks with fp32 accumulators.  The reduction runs in K-steps of
-// 64 through two LDS slots.  Operand tiles travel global memory -> LDS directly
-// (global_load_lds_dwordx4): no staging registers, no LDS write instructions, and the data in flight
-// lives in LDS, so a load has a whole K-step of MFMAs to land (HBM latency under load exceeds what a
-// register-staged pipeline of this tile size can cover).  Two waves per SIMD let the matrix pipe take
-// MFMAs from one wave while the other issues LDS reads and loads.  K-steps are 64 wide so that a load
-// instruction of a reduction-contiguous operand covers 8 rows x 128 bytes, i.e. whole cache lines
+// 64.  Operand tiles travel global memory -> LDS directly (global_load_lds_dwordx4): no staging
+// registers, no LDS write instructions, and the data in flight lives in LDS.  K-steps are 64 wide so that
+// a load instruction of a reduction-contiguous operand covers 8 rows x 128 bytes, i.e. whole cache lines
 // (with 32-wide steps each line is fetched in two halves and such loads cost twice as much).
 //
-// Operand tile formats in one LDS slot (32 KiB per operand):
+// A direct-to-LDS load holds its wave's instruction issue for tens of cycles (more when the memory
+// pipeline is backed up), during which that wave issues no MFMA.  The loop therefore splits the loading
+// between the two waves of each SIMD and staggers it by half a K-step: waves 0-3 load the A operand in the
+// second quarter of a K-step, waves 4-7 the B operand in the fourth, so that one wave of every SIMD is
+// always free to feed the matrix pipe.  To give those loads room, the LDS (all 160 KiB) is a ring of five
+// 32 KiB units, each holding one operand of one K-step: A(kt), B(kt), A(kt+1), B(kt+1) resident or landing,
+// plus one unit being refilled (see kloop).
+//
+// Operand tile formats in one unit:
 //   format K - the operand's reduction index is contiguous in memory (element (r,k) at base[r*ld + k]):
 //              256 rows of 128 bytes, 16-byte chunks XOR-swizzled with bits 1..3 of the row so that the
 //              16 consecutive rows a quarter-wave reads (same chunk) hit 16 different bank groups of the
@@ -39,10 +44,10 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int NTHREADS = 512;                     // 8 waves: 2 (M) x 4 (N), wave tile 128 x 64
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int A_BYTES = BM * BK * 2;              // 32 KiB
-constexpr int STAGE_BYTES = (BM + BN) * BK * 2;   // 64 KiB
-constexpr int SMEM_BYTES = 2 * STAGE_BYTES;       // 128 KiB of the CU's 160 KiB
-constexpr int NLD = 4;                            // load instructions per wave, operand and K-step
+constexpr int UNIT_BYTES = BM * BK * 2;           // 32 KiB: one operand, one K-step
+constexpr int NUNITS = 5;
+constexpr int SMEM_BYTES = NUNITS * UNIT_BYTES;   // all 160 KiB of the CU's LDS
+constexpr int NLD = 8;                            // load instructions per loading wave and unit
 
 enum { FMT_K = 0, FMT_R = 1 };
 
@@ -85,8 +90,10 @@ struct Operand {
   uint32_t rd[4];           // FMT_K: rd[ks] base for sub-step ks; FMT_R: rd[i] base for fragment i
   uint32_t lds_q;           // LDS byte offset (inside the operand tile) of the wave's first load instruction
 
-  // row0: first tile row of this wave's fragments (multiple of 32); ld in elements
-  __device__ __forceinline__ void init(int64_t ld, int wave, int lane, int row0) {
+  // lw: index 0..3 of this wave among the four that load this operand; row0: first tile row of this
+  // wave's fragments (multiple of 32); ld in elements
+  __device__ __forceinline__ void init(int64_t ld, int lw, int lane, int row0) {
+    const int wave = lw;
     lds_q = NLD * wave * 1024;
 #pragma unroll
     for (int n = 0; n < NLD; ++n) {
@@ -114,7 +121,7 @@ struct Operand {
       }
     }
   }
-  // issue this wave's loads of the K-step whose tile starts at `base` into the operand tile at `lds`
+  // issue this wave's loads of the K-step whose tile starts at `base` into the unit at `lds`
   __device__ __forceinline__ void load(const uint16_t* base, char* lds) const {
     char* l0 = lds + __builtin_amdgcn_readfirstlane(lds_q);
 #pragma unroll
@@ -135,21 +142,125 @@ __device__ __forceinline__ u32x4 read_frag(const Operand<FMT, NFRAG>& op, uint32
   return join(ds_read64_tr<KS * 8192>(tile + op.rd[I]), ds_read64_tr<KS * 8192 + 2048>(tile + op.rd[I]));
 }
 template <int FA, int FB, int KS>
-__device__ __forceinline__ void read_frags(Frags& f, const Operand<FA, 4>& a, const Operand<FB, 2>& b, uint32_t stage) {
-  f.a[0] = read_frag<FA, 4, KS, 0>(a, stage);
-  f.b[0] = read_frag<FB, 2, KS, 0>(b, stage + A_BYTES);
-  f.a[1] = read_frag<FA, 4, KS, 1>(a, stage);
-  f.b[1] = read_frag<FB, 2, KS, 1>(b, stage + A_BYTES);
-  f.a[2] = read_frag<FA, 4, KS, 2>(a, stage);
-  f.a[3] = read_frag<FA, 4, KS, 3>(a, stage);
+__device__ __forceinline__ void read_frags(Frags& f, const Operand<FA, 4>& a, const Operand<FB, 2>& b, uint32_t ta, uint32_t tb) {
+  f.a[0] = read_frag<FA, 4, KS, 0>(a, ta);
+  f.b[0] = read_frag<FB, 2, KS, 0>(b, tb);
+  f.a[1] = read_frag<FA, 4, KS, 1>(a, ta);
+  f.b[1] = read_frag<FB, 2, KS, 1>(b, tb);
+  f.a[2] = read_frag<FA, 4, KS, 2>(a, ta);
+  f.a[3] = read_frag<FA, 4, KS, 3>(a, ta);
+}
+__device__ __forceinline__ void mfma1(f32x16& c, const u32x4& a, const u32x4& b) {
+  c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 __device__ __forceinline__ void mfma_block(const Frags& f, f32x16 (&acc)[4][2]) {
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[i]), __builtin_bit_cast(bf16x8, f.b[j]),
-                                                          acc[i][j], 0, 0, 0);
+    for (int j = 0; j < 2; ++j) mfma1(acc[i][j], f.a[i], f.b[j]);
+}
+// the 8 MFMAs of a sub-step with this wave's 8 load instructions of one unit interleaved
+template <int FMT, int NFRAG>
+__device__ __forceinline__ void mfma_block_loads(const Frags& f, f32x16 (&acc)[4][2], const Operand<FMT, NFRAG>& op,
+                                                 const uint16_t* base, char* lds) {
+  char* l0 = lds + __builtin_amdgcn_readfirstlane(op.lds_q);
+#define DISCO_LD(n)                                                                                                         \
+  __builtin_amdgcn_global_load_lds(                                                                                         \
+      (const __attribute__((address_space(1))) void*)(reinterpret_cast<const char*>(base) + op.ld_off[n]),                  \
+      (__attribute__((address_space(3))) void*)(l0 + n * 1024), 16, 0, 0)
+  mfma1(acc[0][0], f.a[0], f.b[0]); DISCO_LD(0);
+  mfma1(acc[0][1], f.a[0], f.b[1]); DISCO_LD(1);
+  mfma1(acc[1][0], f.a[1], f.b[0]); DISCO_LD(2);
+  mfma1(acc[1][1], f.a[1], f.b[1]); DISCO_LD(3);
+  mfma1(acc[2][0], f.a[2], f.b[0]); DISCO_LD(4);
+  mfma1(acc[2][1], f.a[2], f.b[1]); DISCO_LD(5);
+  mfma1(acc[3][0], f.a[3], f.b[0]); DISCO_LD(6);
+  mfma1(acc[3][1], f.a[3], f.b[1]); DISCO_LD(7);
+#undef DISCO_LD
+}
+
+__device__ __forceinline__ int ring_next(int u, int step) { u += step; return u >= NUNITS ? u - NUNITS : u; }
+
+// The K loop of one wave group.  GROUP 0 (waves 0-3) loads the A units, GROUP 1 (waves 4-7) the B units.
+//
+// Ring of five units; the operand tiles are laid into it in the order A0 B0 A1 B1 A2 B2 ..., item n in
+// unit n mod 5.  K-step kt computes from A(kt), B(kt) in four 16-wide sub-steps, each fetching the next
+// sub-step's fragments while its MFMAs run:
+//   sub-step 0;
+//   sub-step 1: group 0 issues the loads of A(kt+2) into the unit that held B(kt-1);
+//   sub-step 2, then: wait for this wave's loads of K-step kt+1 (group 0 may leave the 8 loads of A(kt+2)
+//       in flight, group 1 has nothing younger), wait for its own LDS reads, barrier: K-step kt+1 is complete
+//       in LDS and nobody reads the units of K-step kt any more (the last fragments are in registers);
+//   sub-step 3: group 1 issues the loads of B(kt+2) into the unit that held A(kt); the first fragments of
+//       K-step kt+1 are fetched.
+// So an A load has six sub-steps to land and a B load four.  Loads past the end are clamped to the last
+// K-step (redundant, never out of range, into a unit nobody reads again).
+// READS_FIRST: issue a sub-step's LDS reads ahead of its MFMAs (otherwise the compiler places them).
+template <int FA, int FB, int GROUP, bool READS_FIRST>
+__device__ __forceinline__ void kloop(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bp, int64_t ldb,
+                                      int ktiles, char* smem, f32x16 (&acc)[4][2]) {
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int64_t stepA = FA == FMT_K ? BK : (int64_t)BK * lda;
+  const int64_t stepB = FB == FMT_K ? BK : (int64_t)BK * ldb;
+  const int last = ktiles - 1;
+  Operand<FA, 4> oa;
+  Operand<FB, 2> ob;
+  oa.init(lda, wave & 3, lane, (wave >> 2) * 128);
+  ob.init(ldb, wave & 3, lane, (wave & 3) * 64);
+  const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;   // LDS byte address
+  const int k1 = last < 1 ? last : 1;
+  if (GROUP == 0) {
+    oa.load(A, smem);
+    oa.load(A + k1 * stepA, smem + 2 * UNIT_BYTES);
+  } else {
+    ob.load(Bp, smem + UNIT_BYTES);
+    ob.load(Bp + k1 * stepB, smem + 3 * UNIT_BYTES);
+  }
+  wait_vmcnt<NLD>();
+  lds_barrier();
+  Frags f0, f1;
+  read_frags<FA, FB, 0>(f0, oa, ob, smem_addr, smem_addr + UNIT_BYTES);
+  wait_frags(f0);
+
+  int rA = 0;                                       // unit of A(kt); B(kt) is the next unit of the ring
+  for (int kt = 0; kt < ktiles; ++kt) {
+    const int rB = ring_next(rA, 1), nA = ring_next(rA, 2), nB = ring_next(rA, 3), lA = ring_next(rA, 4);
+    const uint32_t ta = smem_addr + (uint32_t)(rA * UNIT_BYTES), tb = smem_addr + (uint32_t)(rB * UNIT_BYTES);
+    const int kload = kt + 2 < ktiles ? kt + 2 : last;
+    // sub-step 0
+    read_frags<FA, FB, 1>(f1, oa, ob, ta, tb);
+    if (READS_FIRST) __builtin_amdgcn_sched_barrier(0);
+    mfma_block(f0, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_frags(f1);
+    // sub-step 1
+    read_frags<FA, FB, 2>(f0, oa, ob, ta, tb);
+    if (READS_FIRST) __builtin_amdgcn_sched_barrier(0);
+    if (GROUP == 0) mfma_block_loads(f1, acc, oa, A + kload * stepA, smem + lA * UNIT_BYTES);
+    else mfma_block(f1, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_frags(f0);
+    // sub-step 2
+    read_frags<FA, FB, 3>(f1, oa, ob, ta, tb);
+    if (READS_FIRST) __builtin_amdgcn_sched_barrier(0);
+    mfma_block(f0, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    if (GROUP == 0) wait_vmcnt<NLD>(); else wait_vmcnt<0>();
+    wait_frags(f1);
+    asm volatile("s_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    // sub-step 3
+    read_frags<FA, FB, 0>(f0, oa, ob, smem_addr + (uint32_t)(nA * UNIT_BYTES), smem_addr + (uint32_t)(nB * UNIT_BYTES));
+    if (READS_FIRST) __builtin_amdgcn_sched_barrier(0);
+    if (GROUP == 1) mfma_block_loads(f1, acc, ob, Bp + kload * stepB, smem + rA * UNIT_BYTES);
+    else mfma_block(f1, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_frags(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    rA = nA;
+  }
+  wait_vmcnt<0>();
+  lds_barrier();
 }
 
 // acc[bm][bn] += A_tile(256 x K) * B_tile(256 x K)^T for this wave's 128 x 64 piece.
@@ -157,75 +268,11 @@ __device__ __forceinline__ void mfma_block(const Frags& f, f32x16 (&acc)[4][2]) 
 //   A, Bp   : element (row 0, k 0) of the workgroup's operand tiles; ktiles = K / 64 >= 1.
 //   smem    : SMEM_BYTES of LDS, 16-byte aligned; on return no load is in flight and every wave has passed
 //             a barrier, so the caller may reuse it at once.
-//
-// Pipeline over two LDS slots; step kt computes from slot kt & 1 in four 16-wide sub-steps, each fetching
-// the next sub-step's fragments while its MFMAs run:
-//   sub-steps 0..2;
-//   wait for this wave's loads of K-step kt+1 (vmcnt 0) and its own LDS reads, barrier: K-step kt+1 is
-//       complete in the other slot and nobody reads this slot any more (the last fragments are in registers);
-//   sub-step 3: issue the loads of K-step kt+2 into this slot, fetch the first fragments of step kt+1.
-// A load therefore has four sub-steps (one K-step of MFMAs) to land.  Loads past the end are clamped to
-// the last K-step (redundant, never out of range).
-template <int FA, int FB>
+template <int FA, int FB, bool READS_FIRST>
 __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bp,
                                          int64_t ldb, int ktiles, char* smem, f32x16 (&acc)[4][2]) {
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int64_t stepA = FA == FMT_K ? BK : (int64_t)BK * lda;
-  const int64_t stepB = FB == FMT_K ? BK : (int64_t)BK * ldb;
-  const int last = ktiles - 1;
-  Operand<FA, 4> oa;
-  Operand<FB, 2> ob;
-  oa.init(lda, wave, lane, (wave >> 2) * 128);
-  ob.init(ldb, wave, lane, (wave & 3) * 64);
-  const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;   // LDS byte address
-
-  oa.load(A, smem);
-  ob.load(Bp, smem + A_BYTES);
-  {
-    const int k1 = last < 1 ? last : 1;
-    oa.load(A + k1 * stepA, smem + STAGE_BYTES);
-    ob.load(Bp + k1 * stepB, smem + STAGE_BYTES + A_BYTES);
-  }
-  wait_vmcnt<2 * NLD>();
-  lds_barrier();
-  Frags f0, f1;
-  read_frags<FA, FB, 0>(f0, oa, ob, smem_addr);
-  wait_frags(f0);
-
-  for (int kt = 0; kt < ktiles; ++kt) {
-    const int slot = kt & 1;
-    const uint32_t cur = smem_addr + (uint32_t)(slot * STAGE_BYTES);
-    const uint32_t nxt = smem_addr + (uint32_t)((slot ^ 1) * STAGE_BYTES);
-    const int kload = kt + 2 < ktiles ? kt + 2 : last;
-    // sub-step 0
-    read_frags<FA, FB, 1>(f1, oa, ob, cur);
-    mfma_block(f0, acc);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_frags(f1);
-    // sub-step 1
-    read_frags<FA, FB, 2>(f0, oa, ob, cur);
-    mfma_block(f1, acc);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_frags(f0);
-    // sub-step 2
-    read_frags<FA, FB, 3>(f1, oa, ob, cur);
-    mfma_block(f0, acc);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_vmcnt<0>();
-    wait_frags(f1);
-    asm volatile("s_barrier" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
-    // sub-step 3
-    oa.load(A + kload * stepA, smem + slot * STAGE_BYTES);
-    ob.load(Bp + kload * stepB, smem + slot * STAGE_BYTES + A_BYTES);
-    read_frags<FA, FB, 0>(f0, oa, ob, nxt);
-    mfma_block(f1, acc);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_frags(f0);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  wait_vmcnt<0>();
-  lds_barrier();
+  if (threadIdx.x < NTHREADS / 2) kloop<FA, FB, 0, READS_FIRST>(A, lda, Bp, ldb, ktiles, smem, acc);
+  else kloop<FA, FB, 1, READS_FIRST>(A, lda, Bp, ldb, ktiles, smem, acc);
 }
 
 // Writes a workgroup's 256 x 256 fp32 accumulator tile to row-major global memory through LDS, so that
