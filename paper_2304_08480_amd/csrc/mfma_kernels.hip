@@ -54,7 +54,7 @@ struct BlockPtrs {
   float* ediag;          // b: numerator of the label column
   float* zd2;            // b: z2 of the positive pair
   float* xnorm;          // b: |x_i|
-  const uint32_t* ymax2; // 1: bit pattern of max_j |y_j|^2
+  const float* ymax2;    // 1: max_j |y_j|^2
   float* beta;           // b
   float* gdiag;          // b: P_label - 1
   float* ce;             // b
@@ -71,17 +71,15 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-__global__ void k_zero2(uint32_t* p) { if (threadIdx.x < 2) p[threadIdx.x] = 0u; }
-
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// max over all rows of |row|^2 for I (slot 0) and T (slot 1).  A wave takes 8 rows at a time (one 16-byte
-// load per lane and row in flight, d is a multiple of 8), reduces the 8 row sums with interleaved
-// butterflies, and keeps a running maximum; one atomicMax per workgroup (max is order-independent, so the
-// result is deterministic; values are >= 0 so the bit patterns order like floats).
-__global__ __launch_bounds__(256) void k_rownorm_max(const uint16_t* I, const uint16_t* T, int64_t B, int64_t d,
-                                                      uint32_t* out) {
+constexpr int NORM_BLOCKS = 512;     // workgroups per matrix in k_rownorm_max = partial maxima per matrix
+
+// Partial maxima over rows of |row|^2 for I (blockIdx.y = 0) and T (1): out[which * NORM_BLOCKS + blockIdx.x].
+// A wave takes 8 rows at a time (one 16-byte load per lane and row in flight, d is a multiple of 8) and
+// reduces the 8 row sums with interleaved butterflies.  No atomics: k_prep_diag folds the partial maxima.
+__global__ __launch_bounds__(256) void k_rownorm_max(const uint16_t* I, const uint16_t* T, int64_t B, int64_t d, float* out) {
   __shared__ float red[4];
   const int which = blockIdx.y;
   const uint16_t* M = which == 0 ? I : T;
@@ -115,14 +113,26 @@ __global__ __launch_bounds__(256) void k_rownorm_max(const uint16_t* I, const ui
   }
   if (lane == 0) red[wave] = best;
   __syncthreads();
-  if (threadIdx.x == 0) atomicMax(out + which, __float_as_uint(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]))));
+  if (threadIdx.x == 0) out[which * NORM_BLOCKS + blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
-// positive-pair logit and query norm of every local row; one wave per (block, row)
-__global__ __launch_bounds__(256) void k_prep_diag(Blocks bl, int64_t b, int64_t d, int rank, float s2) {
+// positive-pair logit and query norm of every local row; one wave per (block, row).  The first workgroup of
+// each grid row also folds the partial maxima of matrix blockIdx.y into ymax2[blockIdx.y] (max is exact, so the
+// order does not matter).
+__global__ __launch_bounds__(256) void k_prep_diag(Blocks bl, int64_t b, int64_t d, int rank, float s2, const float* wgmax,
+                                                   float* ymax2) {
+  __shared__ float red[4];
+  const int lane = threadIdx.x & 63;
+  if (blockIdx.x == 0) {
+    float m = 0.f;
+    for (int q = threadIdx.x; q < NORM_BLOCKS; q += 256) m = fmaxf(m, wgmax[blockIdx.y * NORM_BLOCKS + q]);
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (lane == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) ymax2[blockIdx.y] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  }
   const BlockPtrs& p = bl.z[blockIdx.y];
   const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
   if (i >= b) return;
   const uint16_t* x = p.X + i * d;
   const uint16_t* y = p.Y + ((int64_t)rank * b + i) * d;
@@ -170,7 +180,7 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3, half = lane >> 5;
-  const float ymax = sqrtf(__uint_as_float(*p.ymax2));
+  const float ymax = sqrtf(*p.ymax2);
   const int64_t lab0 = (int64_t)rank * b;      // label of query row i is key row lab0 + i
   const bool diag_tile = (lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN);
   // The numerators leave through LDS: each lane holds 4 consecutive key columns of 32 different query
@@ -326,39 +336,48 @@ __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b
   store_tile_f32<ACCUMULATE>(acc, smem, p.part + (int64_t)ks * b * d + i0 * d + k0, d, 1.0f);
 }
 
-// Query-side gradient of one local row: gq[label_i][:] += cs (beta_i sum_ks part + gdiag_i y_label), the
-// label-column term of the key-side gradient gk[label_i][:] += cs gdiag_i x_i, and the row's share of
-// d/ds, <query-side vector, x_i>.  Block A's gq is block C's gk, so the two blocks run one after the other.  One workgroup per (block, row), fixed summation order.
-__global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int z, int64_t b, int64_t d, int rank, float cs, int splitk) {
+// Everything that lands in the rank's own rows, for both blocks at once.  With lab = label of local row i:
+//   gI[lab] += cs (beta^A_i sum_ks part^A + gdiag^A_i T[lab])    query side of block A (Eq. 4)
+//            + cs gdiag^C_i T[lab]                                label-column term of block C's key side
+//   gT[lab] += cs (beta^C_i sum_ks part^C + gdiag^C_i I[lab]) + cs gdiag^A_i I[lab]
+// and the rows' shares of d/ds, <query-side vector, x_i>, per block.  One wave per row, fixed summation order.
+__global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int64_t b, int64_t d, int rank, float cs, int splitk) {
   typedef __attribute__((ext_vector_type(4))) float f32x4;
-  const BlockPtrs& p = bl.z[z];
+  const BlockPtrs& pa = bl.z[0];
+  const BlockPtrs& pc = bl.z[1];
   const int lane = threadIdx.x & 63;
-  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // one wave per local row
+  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (i >= b) return;
   const int64_t lab = (int64_t)rank * b + i;
-  const float beta = p.beta[i], gd = p.gdiag[i];
-  float dot = 0.f;
+  const float beta_a = pa.beta[i], gd_a = pa.gdiag[i], beta_c = pc.beta[i], gd_c = pc.gdiag[i];
+  float dot_a = 0.f, dot_c = 0.f;
   for (int64_t k = lane * 4; k < d; k += 256) {
-    f32x4 u = {0.f, 0.f, 0.f, 0.f};
-    for (int ks = 0; ks < splitk; ++ks) u += *reinterpret_cast<const f32x4*>(p.part + ((int64_t)ks * b + i) * d + k);
-    const u32x2 yw = *reinterpret_cast<const u32x2*>(p.Yraw + lab * d + k);
-    const u32x2 xw = *reinterpret_cast<const u32x2*>(p.X + i * d + k);
-    const float yv[4] = {bf16_lo(yw[0]), bf16_hi(yw[0]), bf16_lo(yw[1]), bf16_hi(yw[1])};
-    const float xv[4] = {bf16_lo(xw[0]), bf16_hi(xw[0]), bf16_lo(xw[1]), bf16_hi(xw[1])};
-    f32x4 gq = *reinterpret_cast<f32x4*>(p.gq + lab * d + k);
-    f32x4 gk = *reinterpret_cast<f32x4*>(p.gk + lab * d + k);
+    f32x4 ua = {0.f, 0.f, 0.f, 0.f}, uc = {0.f, 0.f, 0.f, 0.f};
+    for (int ks = 0; ks < splitk; ++ks) {
+      ua += *reinterpret_cast<const f32x4*>(pa.part + ((int64_t)ks * b + i) * d + k);
+      uc += *reinterpret_cast<const f32x4*>(pc.part + ((int64_t)ks * b + i) * d + k);
+    }
+    const u32x2 iw = *reinterpret_cast<const u32x2*>(pa.X + i * d + k);        // I[lab]
+    const u32x2 tw = *reinterpret_cast<const u32x2*>(pc.X + i * d + k);        // T[lab]
+    const float iv[4] = {bf16_lo(iw[0]), bf16_hi(iw[0]), bf16_lo(iw[1]), bf16_hi(iw[1])};
+    const float tv[4] = {bf16_lo(tw[0]), bf16_hi(tw[0]), bf16_lo(tw[1]), bf16_hi(tw[1])};
+    f32x4 gi = *reinterpret_cast<f32x4*>(pa.gq + lab * d + k);
+    f32x4 gt = *reinterpret_cast<f32x4*>(pc.gq + lab * d + k);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const float g = fmaf(beta, u[e], gd * yv[e]);
-      gq[e] = fmaf(cs, g, gq[e]);
-      gk[e] = fmaf(cs * gd, xv[e], gk[e]);      // label-column term of the key-side gradient
-      dot = fmaf(g, xv[e], dot);
+      const float ga = fmaf(beta_a, ua[e], gd_a * tv[e]);
+      const float gc = fmaf(beta_c, uc[e], gd_c * iv[e]);
+      gi[e] = fmaf(cs * gd_c, tv[e], fmaf(cs, ga, gi[e]));
+      gt[e] = fmaf(cs * gd_a, iv[e], fmaf(cs, gc, gt[e]));
+      dot_a = fmaf(ga, iv[e], dot_a);
+      dot_c = fmaf(gc, tv[e], dot_c);
     }
-    *reinterpret_cast<f32x4*>(p.gq + lab * d + k) = gq;
-    *reinterpret_cast<f32x4*>(p.gk + lab * d + k) = gk;
+    *reinterpret_cast<f32x4*>(pa.gq + lab * d + k) = gi;
+    *reinterpret_cast<f32x4*>(pc.gq + lab * d + k) = gt;
   }
-  dot = wave_sum(dot);
-  if (lane == 0) p.rowds[i] = dot;
+  dot_a = wave_sum(dot_a);
+  dot_c = wave_sum(dot_c);
+  if (lane == 0) { pa.rowds[i] = dot_a; pc.rowds[i] = dot_c; }
 }
 
 // loss_r = c sum ce, gs_r = c sum rowds over both blocks; one workgroup, fixed order.
@@ -421,7 +440,7 @@ Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused) {
   pl.off_rows = o;   o += 2 * 7 * pl.rows_stride;   // ediag, zd2, xnorm, beta, gdiag, ce, rowds
   pl.off_Xs = o;     o += 2 * align_up((size_t)d * b * 2);
   pl.off_part = o;   o += 2 * align_up((size_t)pl.splitk * b * d * 4);
-  pl.off_ymax = o;   o += 256;
+  pl.off_ymax = o;   o += 256 + align_up((size_t)2 * NORM_BLOCKS * 4);
   pl.total = o;
   return pl;
 }
@@ -446,7 +465,8 @@ int mfma_run(const Problem& pr, bool fused) {
   char* ws = static_cast<char*>(pr.ws);
   const uint16_t* I = static_cast<const uint16_t*>(pr.I);
   const uint16_t* T = static_cast<const uint16_t*>(pr.T);
-  uint32_t* ymax = reinterpret_cast<uint32_t*>(ws + pl.off_ymax);   // [0] = max |I_j|^2, [1] = max |T_j|^2
+  float* ymax = reinterpret_cast<float*>(ws + pl.off_ymax);         // [0] = max |I_j|^2, [1] = max |T_j|^2
+  float* wgmax = ymax + 64;                                         // 2 x NORM_BLOCKS partial maxima
 
   Blocks bl;
   for (int z = 0; z < 2; ++z) {
@@ -489,9 +509,8 @@ int mfma_run(const Problem& pr, bool fused) {
   int stage = 0;
 
   stage_mark(st, stage++);
-  k_zero2<<<1, 64, 0, st>>>(ymax);
-  k_rownorm_max<<<dim3((unsigned)((B + 31) / 32 < 1024 ? (B + 31) / 32 : 1024), 2), 256, 0, st>>>(I, T, B, d, ymax);
-  k_prep_diag<<<dim3((unsigned)((b + 3) / 4), 2), 256, 0, st>>>(bl, b, d, pr.rank, s2);
+  k_rownorm_max<<<dim3(NORM_BLOCKS, 2), 256, 0, st>>>(I, T, B, d, wgmax);
+  k_prep_diag<<<dim3((unsigned)((b + 3) / 4), 2), 256, 0, st>>>(bl, b, d, pr.rank, s2, wgmax, ymax);
   stage_mark(st, stage++);
 
   int nJp;
@@ -524,8 +543,7 @@ int mfma_run(const Problem& pr, bool fused) {
       k_query_partial<false><<<q_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, jp0, W, pl.nMq, pl.nN, pl.splitk, pl.ktps);
   }
   stage_mark(st, stage++);
-  k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, 0, b, d, pr.rank, cs, pl.splitk);
-  k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, 1, b, d, pr.rank, cs, pl.splitk);
+  k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, b, d, pr.rank, cs, pl.splitk);
   k_scalars<<<1, 1024, 0, st>>>(bl, b, c, pr.accumulate, pr.loss, pr.gs);
   stage_mark(st, stage++);
   return hipGetLastError() == hipSuccess ? DISCO_OK : DISCO_ERR_HIP;
