@@ -147,53 +147,25 @@ __global__ __launch_bounds__(256) void k_prep_diag(Blocks bl, int64_t b, int64_t
   if (lane == 0) { p.zd2[i] = s2 * dot; p.xnorm[i] = sqrtf(nn); }
 }
 
-// Logit tile + softmax numerators for the key panel [jp0, jp0 + W).  Tile rows (MFMA M side) are key rows
-// j, tile columns (N side) are query rows i, so that each lane holds 4 consecutive j of one query row per
-// accumulator quad: 8-byte pieces of a row-major E row and an in-lane row sum.
-//   STATS: write the partial row sums and the label-column numerator (forward statistics);
-//   STORE: write the bf16 numerators to E (row stride W, panel-relative columns).
-// materialized path: STATS and STORE, one panel = all keys.  fused path: a STATS-only pass over all
-// keys (nothing of size b x B is written), then STORE-only passes that recompute one panel at a time.
-template <bool STATS, bool STORE>
-__global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2,
-                                                          int64_t jp0, int64_t W, int nIp, int nJp) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  const BlockPtrs& p = bl.z[blockIdx.y];
-  int lin;
-  if (!xcd_linear(nIp * nJp, lin)) return;
-  // super-blocks of 8 query tiles x 4 key tiles: 12 operand tiles (3 MiB) feed 32 concurrent workgroups
-  const int sb = lin >> 5, within = lin & 31;
-  const int nSBi = nIp >> 3;
-  const int it = (sb % nSBi) * 8 + (within & 7);
-  const int jt = (sb / nSBi) * 4 + (within >> 3);
-  if ((int64_t)it * BN >= b || (int64_t)jt * BM >= W) return;
-  const int64_t i0 = (int64_t)it * BN, j0 = jp0 + (int64_t)jt * BM;
-
-  f32x16 acc[4][2];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
-
+// Epilogue of one logit tile: numerators from the accumulators, row sums, staging of the bf16 tile in LDS.
+// The numerators leave through LDS: each lane holds 4 consecutive key columns of 32 different query rows,
+// which as direct global stores would be 16-byte fragments; staged as a row-major 256 x 256 bf16 tile (rows
+// padded to 528 bytes: conflict-free 8-byte writes and 16-byte reads) they go out as whole 512-byte row
+// segments.  DIAG: the tile contains label columns, which are stored as 0 and kept in fp32 in ediag.
+template <bool STATS, bool STORE, bool DIAG>
+__device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)[4][2], char* smem, int64_t b, float s2, int64_t i0,
+                                               int64_t j0, int64_t lab0, const float (&ref2)[2]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3, half = lane >> 5;
-  const float ymax = sqrtf(*p.ymax2);
-  const int64_t lab0 = (int64_t)rank * b;      // label of query row i is key row lab0 + i
-  const bool diag_tile = (lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN);
-  // The numerators leave through LDS: each lane holds 4 consecutive key columns of 32 different query
-  // rows, which as direct global stores would be 16-byte fragments; staged as a row-major 256 x 256 bf16
-  // tile (rows padded to 528 bytes: conflict-free 8-byte writes and 16-byte reads) they go out as whole
-  // 512-byte row segments.
 #pragma unroll
   for (int bn = 0; bn < 2; ++bn) {
     const int il = wn * 64 + bn * 32 + (lane & 31);
     const int64_t i = i0 + il;
-    const float zd = p.zd2[i];
-    const float ref = fmaxf(zd, fabsf(s2) * p.xnorm[i] * ymax - REF_HEADROOM);
-    const int64_t lab = lab0 + i;
+    const float ref = ref2[bn];
+    // label column of row i, relative to this lane's first key column of the tile (any value outside
+    // [0, 128) means the label is not among this lane's columns)
+    const int64_t dl64 = lab0 + i - (j0 + wm * 128 + half * 4);
+    const int dl = dl64 >= 0 && dl64 < 128 ? (int)dl64 : -1;
     float rowsum = 0.f;
     char* lrow = smem + il * E_ROW_BYTES;
 #pragma unroll
@@ -204,11 +176,10 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
         float e[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) e[r] = __builtin_amdgcn_exp2f(fmaf(acc[bm][bn][q * 4 + r], s2, -ref));
-        const int64_t j = j0 + jl + q * 8;
-        if (diag_tile && lab >= j && lab < j + 4) {
+        if (DIAG) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            if (lab == j + r) {
+            if (dl == bm * 32 + q * 8 + r) {
               if (STATS) p.ediag[i] = e[r];
               e[r] = 0.f;
             }
@@ -227,15 +198,76 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
       if (half == 0) p.lpart[((j0 >> 7) + wm) * b + i] = rowsum;
     }
   }
-  if (STORE) {
-    lds_barrier();
-    const int t = threadIdx.x;
-    const int chunk = t & 31, r0 = t >> 5;     // 32 chunks of 16 bytes per 512-byte row; 16 rows per pass
+}
+
+// Logit tile + softmax numerators for the key panel [jp0, jp0 + W).  Tile rows (MFMA M side) are key rows
+// j, tile columns (N side) are query rows i, so that each lane holds 4 consecutive j of one query row per
+// accumulator quad: 8-byte pieces of a row-major E row and an in-lane row sum.
+//   STATS: write the partial row sums and the label-column numerator (forward statistics);
+//   STORE: write the bf16 numerators to E (row stride W, panel-relative columns).
+// materialized path: STATS and STORE, one panel = all keys.  fused path: a STATS-only pass over all
+// keys (nothing of size b x B is written), then STORE-only passes that recompute one panel at a time.
+template <bool STATS, bool STORE>
+__global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2,
+                                                          int64_t jp0, int64_t W, int nIp, int nJp) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  // Persistent workgroups (one per compute unit) walk the padded tile lists of block A, then block C, with a
+  // stride of the grid size: a wave ends only when all its stores are acknowledged, so ending a workgroup
+  // per tile would expose that latency and the launch of the next workgroup 16 times per compute unit;
+  // here a tile's stores drain while the next tile's operands are fetched.  gridDim.x is a multiple of 8,
+  // so a workgroup stays on one XCD's slice of the tile list.
+  const int padded = nIp * nJp;                 // multiple of 32
+  const int chunk = padded >> 3;
+  const int lane = threadIdx.x & 63, wn = (threadIdx.x >> 6) & 3;
+  for (int v = blockIdx.x; v < 2 * padded; v += gridDim.x) {
+    const int z = v >= padded ? 1 : 0;
+    const int u = v - z * padded;
+    const BlockPtrs& p = bl.z[z];
+    const int lin = (u & 7) * chunk + (u >> 3);
+    // super-blocks of 8 query tiles x 4 key tiles: 12 operand tiles (3 MiB) feed 32 concurrent workgroups
+    const int sb = lin >> 5, within = lin & 31;
+    const int nSBi = nIp >> 3;
+    const int it = (sb % nSBi) * 8 + (within & 7);
+    const int jt = (sb / nSBi) * 4 + (within >> 3);
+    if ((int64_t)it * BN >= b || (int64_t)jt * BM >= W) continue;     // padding (workgroup-uniform)
+    const int64_t i0 = (int64_t)it * BN, j0 = jp0 + (int64_t)jt * BM;
+
+    // exponent reference of this lane's two query rows, fetched before the main loop so that the loads are
+    // not waited for in the epilogue
+    float ref2[2];
+    {
+      const float ymax = sqrtf(*p.ymax2);
+#pragma unroll
+      for (int bn = 0; bn < 2; ++bn) {
+        const int64_t i = i0 + wn * 64 + bn * 32 + (lane & 31);
+        ref2[bn] = fmaxf(p.zd2[i], fabsf(s2) * p.xnorm[i] * ymax - REF_HEADROOM);
+      }
+    }
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
+
+    const int64_t lab0 = (int64_t)rank * b;      // label of query row i is key row lab0 + i
+    // Only the tiles that the label diagonal crosses pay for finding the label column.
+    if ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) logit_epilogue<STATS, STORE, true>(p, acc, smem, b, s2, i0, j0, lab0, ref2);
+    else logit_epilogue<STATS, STORE, false>(p, acc, smem, b, s2, i0, j0, lab0, ref2);
+    if (STORE) {
+      lds_barrier();
+      const int t = threadIdx.x;
+      const int chunk16 = t & 31, r0 = t >> 5;   // 32 chunks of 16 bytes per 512-byte row; 16 rows per pass
 #pragma unroll 8
-    for (int r = 0; r < 16; ++r) {
-      const int row = r * 16 + r0;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + chunk * 16);
-      *reinterpret_cast<u32x4*>(p.E + (i0 + row) * W + (j0 - jp0) + chunk * 8) = v;
+      for (int r = 0; r < 16; ++r) {
+        const int row = r * 16 + r0;
+        const u32x4 val = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + chunk16 * 16);
+        // written once, read by later kernels: streaming stores keep the operand tiles in L2
+        __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(p.E + (i0 + row) * W + (j0 - jp0) + chunk16 * 8));
+      }
+      lds_barrier();                             // the staged tile has been read: the next tile may load into LDS
     }
   }
 }
@@ -445,6 +477,13 @@ Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused) {
   return pl;
 }
 
+// Compute units of the current device rounded down to a multiple of 8 (one persistent workgroup each).
+int compute_units() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+  return n / 8 * 8;
+}
+
 template <class K>
 bool allow_lds(K kernel, int bytes) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess;
@@ -461,6 +500,7 @@ int mfma_run(const Problem& pr, bool fused) {
     attr_set = true;
   }
   const Plan pl = make_plan(pr.B, pr.d, pr.N, fused);
+  const int persistent_wgs = compute_units();
   const int64_t b = pl.b, B = pl.B, d = pl.d, W = pl.W;
   char* ws = static_cast<char*>(pr.ws);
   const uint16_t* I = static_cast<const uint16_t*>(pr.I);
@@ -501,7 +541,8 @@ int mfma_run(const Problem& pr, bool fused) {
   auto logit_grid = [&](int64_t keys, int& nJp) {
     const int nJ = (int)(keys / BM);
     nJp = (nJ + 3) / 4 * 4;
-    return dim3((unsigned)(((nIp * nJp + 7) / 8) * 8), 2);
+    const int tiles2 = 2 * nIp * nJp;              // both blocks, padded (multiple of 64)
+    return dim3((unsigned)(tiles2 < persistent_wgs ? tiles2 : persistent_wgs));
   };
   const int nMk = (int)(W / BM);
   const dim3 key_grid((unsigned)(((nMk * pl.nN + 7) / 8) * 8), 2);
