@@ -209,9 +209,9 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
 // keys (nothing of size b x B is written), then STORE-only passes that recompute one panel at a time.
 template <bool STATS, bool STORE>
 __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2,
-                                                          int64_t jp0, int64_t W, int nIp, int nJp) {
+                                                          int64_t jp0, int64_t W, int nIp, int nJp, int nblk) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  // Persistent workgroups (one per compute unit) walk the padded tile lists of block A, then block C, with a
+  // Persistent workgroups (one per compute unit) walk the padded tile lists of the nblk blocks in bl, one after the other, with a
   // stride of the grid size: a wave ends only when all its stores are acknowledged, so ending a workgroup
   // per tile would expose that latency and the launch of the next workgroup 16 times per compute unit;
   // here a tile's stores drain while the next tile's operands are fetched.  gridDim.x is a multiple of 8,
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
   const int padded = nIp * nJp;                 // multiple of 32
   const int chunk = padded >> 3;
   const int lane = threadIdx.x & 63, wn = (threadIdx.x >> 6) & 3;
-  for (int v = blockIdx.x; v < 2 * padded; v += gridDim.x) {
+  for (int v = blockIdx.x; v < nblk * padded; v += gridDim.x) {
     const int z = v >= padded ? 1 : 0;
     const int u = v - z * padded;
     const BlockPtrs& p = bl.z[z];
@@ -343,14 +343,33 @@ __global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int
 
 // Query-side products, split over the key index: part[ks][i][k] = sum_{j in split ks} E[i][j] y_jk.
 // GEMM M = query rows i, N = feature index k (operand Y read transposed), reduction over key rows.
+// One-dimensional grid over (block z, split ks, row tile mt, column tile nt).  A "slice" is one (z, ks): all
+// its workgroups read the same rows of Y, so slices are pinned to XCDs (workgroups are dealt round-robin to
+// the 8 XCDs): with S = 2 splitk slices, either S/8 slices per XCD one after the other (S a multiple of 8), or
+// 8/S XCDs per slice sharing its tiles (S divides 8).  Then Y comes in from the fabric once per slice instead
+// of once per XCD.  Any other S falls back to slices laid out contiguously.
 template <bool ACCUMULATE>
 __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b, int64_t d, int64_t jp0, int64_t W, int nM,
                                                             int nN, int splitk, int ktiles_per_split) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const BlockPtrs& p = bl.z[blockIdx.y];
-  int lin;
-  if (!xcd_linear(nM * nN * splitk, lin)) return;
-  const int nt = lin % nN, ks = (lin / nN) % splitk, mt = lin / (nN * splitk);
+  const int T = nM * nN, S = 2 * splitk;
+  const int w = blockIdx.x, xcd = w & 7, r = w >> 3;
+  int slice, tile;
+  if (S % 8 == 0) {
+    slice = xcd + 8 * (r / T);
+    tile = r % T;
+  } else if (8 % S == 0) {
+    const int G = 8 / S;
+    slice = xcd % S;
+    tile = xcd / S + G * r;
+  } else {
+    slice = w / T;
+    tile = w % T;
+  }
+  if (slice >= S || tile >= T) return;
+  const BlockPtrs& p = bl.z[slice / splitk];
+  const int ks = slice % splitk;
+  const int nt = tile % nN, mt = tile / nN;
   const int64_t i0 = (int64_t)mt * BM, k0 = (int64_t)nt * BN;
   const int kt_total = (int)(W / BK);
   const int kt0 = ks * ktiles_per_split;
@@ -459,7 +478,10 @@ Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused) {
   pl.nN = (int)(d / BN);
   const int tiles = pl.nMq * pl.nN;
   const int kt_total = (int)(pl.W / BK);
-  int sk = (256 + tiles - 1) / tiles;      // one workgroup per compute unit
+  // split so that both blocks together give about one workgroup per compute unit (256); multiples of 4 make
+  // the number of (block, split) slices a multiple of 8, which k_query_partial can pin to XCDs
+  int sk = (256 + 2 * tiles - 1) / (2 * tiles);
+  if (sk >= 3) sk = (sk + 1) / 4 * 4;
   if (sk > 32) sk = 32;
   if (sk > kt_total) sk = kt_total;
   if (sk < 1) sk = 1;
@@ -546,7 +568,10 @@ int mfma_run(const Problem& pr, bool fused) {
   };
   const int nMk = (int)(W / BM);
   const dim3 key_grid((unsigned)(((nMk * pl.nN + 7) / 8) * 8), 2);
-  const dim3 q_grid((unsigned)(((pl.nMq * pl.nN * pl.splitk + 7) / 8) * 8), 2);
+  // k_query_partial's grid: see its slice -> XCD mapping
+  const int qT = pl.nMq * pl.nN, qS = 2 * pl.splitk;
+  const int q_wgs = qS % 8 == 0 ? 8 * qT * (qS / 8) : 8 % qS == 0 ? 8 * ((qT + 8 / qS - 1) / (8 / qS)) : (qS * qT + 7) / 8 * 8;
+  const dim3 q_grid((unsigned)q_wgs);
   int stage = 0;
 
   stage_mark(st, stage++);
@@ -557,10 +582,10 @@ int mfma_run(const Problem& pr, bool fused) {
   int nJp;
   if (fused) {
     const dim3 g = logit_grid(B, nJp);
-    k_logit_tiles<true, false><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, nIp, nJp);
+    k_logit_tiles<true, false><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, nIp, nJp, 2);
   } else {
     const dim3 g = logit_grid(B, nJp);
-    k_logit_tiles<true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, nIp, nJp);
+    k_logit_tiles<true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, nIp, nJp, 2);
   }
   stage_mark(st, stage++);
   k_row_merge<<<dim3((unsigned)((b + 63) / 64), 2), 256, 0, st>>>(bl, b, pl.nparts);
@@ -571,7 +596,7 @@ int mfma_run(const Problem& pr, bool fused) {
     const int64_t jp0 = (int64_t)pnl * W;
     if (fused) {
       const dim3 g = logit_grid(W, nJp);
-      k_logit_tiles<false, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, jp0, W, nIp, nJp);
+      k_logit_tiles<false, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, jp0, W, nIp, nJp, 2);
     }
     if (pr.accumulate)
       k_key_grad<true><<<key_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, cs, jp0, W, nMk, pl.nN);
