@@ -49,7 +49,7 @@ struct BlockPtrs {
   const uint16_t* X;     // b x d, the rank's rows
   const uint16_t* Y;     // B x d
   const uint16_t* Yraw;  // same as Y
-  uint16_t* E;           // b x B stored numerators
+  uint16_t* E;           // b x W stored numerators of one key panel, in 64 x 64 blocks (e_index)
   float* lpart;          // (B/128) x b partial row sums (label column excluded)
   float* ediag;          // b: numerator of the label column
   float* zd2;            // b: z2 of the positive pair
@@ -147,6 +147,12 @@ __global__ __launch_bounds__(256) void k_prep_diag(Blocks bl, int64_t b, int64_t
   if (lane == 0) { p.zd2[i] = s2 * dot; p.xnorm[i] = sqrtf(nn); }
 }
 
+// Element (i, jl) of a stored numerator panel of width W: 64 x 64 blocks, block rows contiguous (format
+// FMT_KB / FMT_RB of mfma_tile.h).
+__device__ __forceinline__ int64_t e_index(int64_t i, int64_t jl, int64_t W) {
+  return ((i >> 6) * (W >> 6) + (jl >> 6)) * 4096 + (i & 63) * 64 + (jl & 63);
+}
+
 // Epilogue of one logit tile: numerators from the accumulators, row sums, staging of the bf16 tile in LDS.
 // The numerators leave through LDS: each lane holds 4 consecutive key columns of 32 different query rows,
 // which as direct global stores would be 16-byte fragments; staged as a row-major 256 x 256 bf16 tile (rows
@@ -202,9 +208,9 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
 
 // Logit tile + softmax numerators for the key panel [jp0, jp0 + W).  Tile rows (MFMA M side) are key rows
 // j, tile columns (N side) are query rows i, so that each lane holds 4 consecutive j of one query row per
-// accumulator quad: 8-byte pieces of a row-major E row and an in-lane row sum.
+// accumulator quad: 8-byte pieces of an E row and an in-lane row sum.
 //   STATS: write the partial row sums and the label-column numerator (forward statistics);
-//   STORE: write the bf16 numerators to E (row stride W, panel-relative columns).
+//   STORE: write the bf16 numerators to E (panel-relative columns, 64 x 64 blocked storage, see e_index).
 // materialized path: STATS and STORE, one panel = all keys.  fused path: a STATS-only pass over all
 // keys (nothing of size b x B is written), then STORE-only passes that recompute one panel at a time.
 template <bool STATS, bool STORE>
@@ -265,7 +271,8 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
         const int row = r * 16 + r0;
         const u32x4 val = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + chunk16 * 16);
         // written once, read by later kernels: streaming stores keep the operand tiles in L2
-        __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(p.E + (i0 + row) * W + (j0 - jp0) + chunk16 * 8));
+        const int64_t i = i0 + row, jl = (j0 - jp0) + chunk16 * 8;
+        __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(p.E + e_index(i, jl, W)));
       }
       lds_barrier();                             // the staged tile has been read: the next tile may load into LDS
     }
@@ -337,7 +344,7 @@ __global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  mainloop<FMT_R, FMT_K, true>(p.E + jl0, W, p.Xs + k0 * b, b, (int)(b / BK), smem, acc);
+  mainloop<FMT_RB, FMT_K, true>(p.E + (jl0 >> 6) * 4096, (W >> 6) * 4096, p.Xs + k0 * b, b, (int)(b / BK), smem, acc);
   store_tile_f32<ACCUMULATE>(acc, smem, p.gk + (jp0 + jl0) * d + k0, d, cs);
 }
 
@@ -383,7 +390,7 @@ __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   if (kts > 0)
-    mainloop<FMT_K, FMT_R, false>(p.E + i0 * W + (int64_t)kt0 * BK, W, p.Yraw + (jp0 + (int64_t)kt0 * BK) * d + k0, d, kts, smem, acc);
+    mainloop<FMT_KB, FMT_R, false>(p.E + ((i0 >> 6) * (W >> 6) + kt0) * 4096, (W >> 6) * 4096, p.Yraw + (jp0 + (int64_t)kt0 * BK) * d + k0, d, kts, smem, acc);
   store_tile_f32<ACCUMULATE>(acc, smem, p.part + (int64_t)ks * b * d + i0 * d + k0, d, 1.0f);
 }
 

@@ -28,6 +28,12 @@
 //              ds_read_b64_tr_b16 (two per fragment).
 // A direct-to-LDS load puts lane l's 16 bytes at (wave-uniform LDS base) + 16*l, so a swizzle is applied by
 // choosing which global chunk each lane fetches.
+//
+// FMT_KB / FMT_RB are the same two LDS formats for an operand kept in memory as 64 x 64 blocks (each block
+// 8 KiB, row-major, 128-byte rows; blocks of one block row contiguous; `ld` = elements between block rows):
+// FMT_KB reduces along a block row (a K-step is one block per 64 tile rows), FMT_RB reduces down the block
+// rows (a K-step is one block row, four blocks wide).  A K-step's tile is then four contiguous 8 KiB runs in
+// memory instead of 256 pieces of 128 bytes (or 64 of 512) a row pitch apart, which DRAM serves better.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -49,7 +55,8 @@ constexpr int NUNITS = 5;
 constexpr int SMEM_BYTES = NUNITS * UNIT_BYTES;   // all 160 KiB of the CU's LDS
 constexpr int NLD = 8;                            // load instructions per loading wave and unit
 
-enum { FMT_K = 0, FMT_R = 1 };
+enum { FMT_K = 0, FMT_R = 1, FMT_KB = 2, FMT_RB = 3 };
+constexpr bool fmt_is_k(int f) { return f == FMT_K || f == FMT_KB; }
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
@@ -98,16 +105,19 @@ struct Operand {
 #pragma unroll
     for (int n = 0; n < NLD; ++n) {
       const int q = NLD * wave + n;               // which 1 KiB slice of the 32 KiB tile
-      if (FMT == FMT_K) {
+      if (fmt_is_k(FMT)) {
         const int rho = 8 * q + (lane >> 3), pc = lane & 7;
-        ld_off[n] = (uint32_t)(((int64_t)rho * ld + ((pc ^ ((rho >> 1) & 7)) << 3)) * 2);
+        const int ch = (pc ^ ((rho >> 1) & 7)) << 3;
+        if (FMT == FMT_K) ld_off[n] = (uint32_t)(((int64_t)rho * ld + ch) * 2);
+        else ld_off[n] = (uint32_t)(((int64_t)(rho >> 6) * ld + (rho & 63) * 64 + ch) * 2);
       } else {
         const int kap = 2 * q + (lane >> 5), pcw = lane & 31;
         const int c = (((pcw >> 1) ^ ((kap & 3) << 1)) << 1) | (pcw & 1);
-        ld_off[n] = (uint32_t)(((int64_t)kap * ld + (c << 3)) * 2);
+        if (FMT == FMT_R) ld_off[n] = (uint32_t)(((int64_t)kap * ld + (c << 3)) * 2);
+        else ld_off[n] = (uint32_t)(((c >> 3) * 4096 + kap * 64 + ((c & 7) << 3)) * 2);
       }
     }
-    if (FMT == FMT_K) {
+    if (fmt_is_k(FMT)) {
       const int row = row0 + (lane & 31), g = (row >> 1) & 7, kc = lane >> 5;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) rd[ks] = (uint32_t)(row * 128 + (((ks * 2 + kc) ^ g) << 4));
@@ -138,7 +148,7 @@ __device__ __forceinline__ u32x4 join(u32x2 lo, u32x2 hi) { return u32x4{lo[0], 
 // fragment i of sub-step KS from the operand tile at LDS byte address `tile`
 template <int FMT, int NFRAG, int KS, int I>
 __device__ __forceinline__ u32x4 read_frag(const Operand<FMT, NFRAG>& op, uint32_t tile) {
-  if (FMT == FMT_K) return ds_read128<I * 4096>(tile + op.rd[KS]);
+  if (fmt_is_k(FMT)) return ds_read128<I * 4096>(tile + op.rd[KS]);
   return join(ds_read64_tr<KS * 8192>(tile + op.rd[I]), ds_read64_tr<KS * 8192 + 2048>(tile + op.rd[I]));
 }
 template <int FA, int FB, int KS>
@@ -200,8 +210,8 @@ template <int FA, int FB, int GROUP, bool READS_FIRST>
 __device__ __forceinline__ void kloop(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bp, int64_t ldb,
                                       int ktiles, char* smem, f32x16 (&acc)[4][2]) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int64_t stepA = FA == FMT_K ? BK : (int64_t)BK * lda;
-  const int64_t stepB = FB == FMT_K ? BK : (int64_t)BK * ldb;
+  const int64_t stepA = FA == FMT_K ? BK : FA == FMT_KB ? 4096 : FA == FMT_R ? (int64_t)BK * lda : lda;
+  const int64_t stepB = FB == FMT_K ? BK : FB == FMT_KB ? 4096 : FB == FMT_R ? (int64_t)BK * ldb : ldb;
   const int last = ktiles - 1;
   Operand<FA, 4> oa;
   Operand<FB, 2> ob;
@@ -264,7 +274,8 @@ __device__ __forceinline__ void kloop(const uint16_t* __restrict__ A, int64_t ld
 }
 
 // acc[bm][bn] += A_tile(256 x K) * B_tile(256 x K)^T for this wave's 128 x 64 piece.
-//   FA / FB : tile format of the A / B operand (FMT_K: element (r,k) at base[r*ld + k]; FMT_R: at base[k*ld + r]).
+//   FA / FB : tile format of the A / B operand (FMT_K: element (r,k) at base[r*ld + k]; FMT_R: at base[k*ld + r];
+//             FMT_KB / FMT_RB: the same for 64 x 64 blocked storage, see the top of this file).
 //   A, Bp   : element (row 0, k 0) of the workgroup's operand tiles; ktiles = K / 64 >= 1.
 //   smem    : SMEM_BYTES of LDS, 16-byte aligned; on return no load is in flight and every wave has passed
 //             a barrier, so the caller may reuse it at once.
