@@ -297,8 +297,16 @@ template <bool ACCUMULATE>
 __device__ __forceinline__ void store_tile_f32(f32x16 (&acc)[4][2], char* smem, float* out, int64_t ld, float scale) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 2, wn = wave & 3, half = lane >> 5;
+  const int chunk = t & 63, r0 = t >> 6;
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
+    // when accumulating, the old values are requested eight rows at a time, the first eight before the
+    // staging so that their latency is paid under the LDS traffic
+    f32x4 old[8];
+    if (ACCUMULATE) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) old[r] = *reinterpret_cast<const f32x4*>(out + (int64_t)(h * 128 + r * 8 + r0) * ld + chunk * 4);
+    }
     lds_barrier();
     if (wm == h) {
 #pragma unroll
@@ -313,14 +321,21 @@ __device__ __forceinline__ void store_tile_f32(f32x16 (&acc)[4][2], char* smem, 
           }
     }
     lds_barrier();
-    const int chunk = t & 63, r0 = t >> 6;
-#pragma unroll 4
-    for (int r = 0; r < 16; ++r) {
-      const int row = r * 8 + r0;
-      f32x4 v = *reinterpret_cast<const f32x4*>(smem + row * OUT_ROW_BYTES + chunk * 16);
-      float* g = out + (int64_t)(h * 128 + row) * ld + chunk * 4;
-      if (ACCUMULATE) v += *reinterpret_cast<const f32x4*>(g);
-      *reinterpret_cast<f32x4*>(g) = v;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      f32x4 v[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) v[r] = *reinterpret_cast<const f32x4*>(smem + ((q * 8 + r) * 8 + r0) * OUT_ROW_BYTES + chunk * 16);
+      if (ACCUMULATE && q == 1) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) old[r] = *reinterpret_cast<const f32x4*>(out + (int64_t)(h * 128 + (8 + r) * 8 + r0) * ld + chunk * 4);
+      }
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        float* g = out + (int64_t)(h * 128 + (q * 8 + r) * 8 + r0) * ld + chunk * 4;
+        if (ACCUMULATE) v[r] += old[r];
+        *reinterpret_cast<f32x4*>(g) = v[r];
+      }
     }
   }
 }
