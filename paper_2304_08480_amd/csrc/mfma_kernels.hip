@@ -54,7 +54,7 @@ struct BlockPtrs {
   float* ediag;          // b: numerator of the label column
   float* zd2;            // b: z2 of the positive pair
   float* xnorm;          // b: |x_i|
-  const float* ymax2;    // 1: max_j |y_j|^2
+  const float* ymax_parts; // NORM_BLOCKS partial maxima of |y_j|^2
   float* beta;           // b
   float* gdiag;          // b: P_label - 1
   float* ce;             // b
@@ -74,65 +74,58 @@ __device__ __forceinline__ float wave_sum(float v) {
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-constexpr int NORM_BLOCKS = 512;     // workgroups per matrix in k_rownorm_max = partial maxima per matrix
+constexpr int NORM_BLOCKS = 512;     // workgroups per matrix that take row norms = partial maxima per matrix
+static_assert(NORM_BLOCKS == NTHREADS, "the logit kernel folds the partial maxima one per thread");
 
-// Partial maxima over rows of |row|^2 for I (blockIdx.y = 0) and T (1): out[which * NORM_BLOCKS + blockIdx.x].
-// A wave takes 8 rows at a time (one 16-byte load per lane and row in flight, d is a multiple of 8) and
-// reduces the 8 row sums with interleaved butterflies.  No atomics: k_prep_diag folds the partial maxima.
-__global__ __launch_bounds__(256) void k_rownorm_max(const uint16_t* I, const uint16_t* T, int64_t B, int64_t d, float* out) {
+// Preparation, two kinds of workgroup in one launch (they are independent of each other):
+//  * blockIdx.x < 2 NORM_BLOCKS: partial maximum over rows of |row|^2 of I (first NORM_BLOCKS workgroups) or T,
+//    for the overflow guard, to wgmax[which * NORM_BLOCKS + index].  A wave takes 8 rows at a time (one 16-byte
+//    load per lane and row in flight, d is a multiple of 8) and reduces the 8 row sums with interleaved
+//    butterflies.  No atomics: the consumers fold the partial maxima (max is exact, so order does not matter).
+//  * the rest: positive-pair logit and query norm of every local row, one wave per (block, row).
+__global__ __launch_bounds__(256) void k_prep(Blocks bl, const uint16_t* I, const uint16_t* T, int64_t B, int64_t b, int64_t d, int rank,
+                                              float s2, float* wgmax) {
   __shared__ float red[4];
-  const int which = blockIdx.y;
-  const uint16_t* M = which == 0 ? I : T;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  float best = 0.f;
-  for (int64_t row0 = ((int64_t)blockIdx.x * 4 + wave) * 8; row0 < B; row0 += (int64_t)gridDim.x * 32) {
-    float a[8];
+  if (blockIdx.x < 2 * NORM_BLOCKS) {
+    const int which = blockIdx.x / NORM_BLOCKS, idx = blockIdx.x % NORM_BLOCKS;
+    const uint16_t* M = which == 0 ? I : T;
+    float best = 0.f;
+    for (int64_t row0 = ((int64_t)idx * 4 + wave) * 8; row0 < B; row0 += (int64_t)NORM_BLOCKS * 32) {
+      float a[8];
 #pragma unroll
-    for (int r = 0; r < 8; ++r) a[r] = 0.f;
-    for (int64_t k = lane * 8; k < d; k += 512) {
-      u32x4 v[8];
+      for (int r = 0; r < 8; ++r) a[r] = 0.f;
+      for (int64_t k = lane * 8; k < d; k += 512) {
+        u32x4 v[8];
 #pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        const int64_t row = row0 + r < B ? row0 + r : B - 1;     // clamp: a repeated row does not change the max
-        v[r] = *reinterpret_cast<const u32x4*>(M + row * d + k);
+        for (int r = 0; r < 8; ++r) {
+          const int64_t row = row0 + r < B ? row0 + r : B - 1;     // clamp: a repeated row does not change the max
+          v[r] = *reinterpret_cast<const u32x4*>(M + row * d + k);
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            a[r] = fmaf(bf16_lo(v[r][q]), bf16_lo(v[r][q]), a[r]);
+            a[r] = fmaf(bf16_hi(v[r][q]), bf16_hi(v[r][q]), a[r]);
+          }
       }
 #pragma unroll
-      for (int r = 0; r < 8; ++r)
+      for (int o = 32; o > 0; o >>= 1)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          a[r] = fmaf(bf16_lo(v[r][q]), bf16_lo(v[r][q]), a[r]);
-          a[r] = fmaf(bf16_hi(v[r][q]), bf16_hi(v[r][q]), a[r]);
-        }
+        for (int r = 0; r < 8; ++r) a[r] += __shfl_xor(a[r], o);
+#pragma unroll
+      for (int r = 0; r < 8; ++r) best = fmaxf(best, a[r]);
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1)
-#pragma unroll
-      for (int r = 0; r < 8; ++r) a[r] += __shfl_xor(a[r], o);
-#pragma unroll
-    for (int r = 0; r < 8; ++r) best = fmaxf(best, a[r]);
-  }
-  if (lane == 0) red[wave] = best;
-  __syncthreads();
-  if (threadIdx.x == 0) out[which * NORM_BLOCKS + blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-}
-
-// positive-pair logit and query norm of every local row; one wave per (block, row).  The first workgroup of
-// each grid row also folds the partial maxima of matrix blockIdx.y into ymax2[blockIdx.y] (max is exact, so the
-// order does not matter).
-__global__ __launch_bounds__(256) void k_prep_diag(Blocks bl, int64_t b, int64_t d, int rank, float s2, const float* wgmax,
-                                                   float* ymax2) {
-  __shared__ float red[4];
-  const int lane = threadIdx.x & 63;
-  if (blockIdx.x == 0) {
-    float m = 0.f;
-    for (int q = threadIdx.x; q < NORM_BLOCKS; q += 256) m = fmaxf(m, wgmax[blockIdx.y * NORM_BLOCKS + q]);
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-    if (lane == 0) red[threadIdx.x >> 6] = m;
+    if (lane == 0) red[wave] = best;
     __syncthreads();
-    if (threadIdx.x == 0) ymax2[blockIdx.y] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    if (threadIdx.x == 0) wgmax[which * NORM_BLOCKS + idx] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    return;
   }
-  const BlockPtrs& p = bl.z[blockIdx.y];
-  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t rb = (b + 3) / 4;                       // row workgroups per block
+  const int64_t q = (int64_t)blockIdx.x - 2 * NORM_BLOCKS;
+  const BlockPtrs& p = bl.z[q / rb];
+  const int64_t i = (q % rb) * 4 + wave;
   if (i >= b) return;
   const uint16_t* x = p.X + i * d;
   const uint16_t* y = p.Y + ((int64_t)rank * b + i) * d;
@@ -225,6 +218,26 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
   const int padded = nIp * nJp;                 // multiple of 32
   const int chunk = padded >> 3;
   const int lane = threadIdx.x & 63, wn = (threadIdx.x >> 6) & 3;
+  // max_j |y_j| of each block's key matrix, folded from the partial maxima (one per thread)
+  float ymax_z[2];
+  {
+    float* red = reinterpret_cast<float*>(smem);
+#pragma unroll
+    for (int z = 0; z < 2; ++z) {
+      float m = bl.z[z].ymax_parts[threadIdx.x];
+      for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+      if (lane == 0) red[z * 8 + (threadIdx.x >> 6)] = m;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int z = 0; z < 2; ++z) {
+      float m = red[z * 8];
+#pragma unroll
+      for (int w = 1; w < 8; ++w) m = fmaxf(m, red[z * 8 + w]);
+      ymax_z[z] = sqrtf(m);
+    }
+    __syncthreads();
+  }
   for (int v = blockIdx.x; v < nblk * padded; v += gridDim.x) {
     const int z = v >= padded ? 1 : 0;
     const int u = v - z * padded;
@@ -242,7 +255,7 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
     // not waited for in the epilogue
     float ref2[2];
     {
-      const float ymax = sqrtf(*p.ymax2);
+      const float ymax = z ? ymax_z[1] : ymax_z[0];
 #pragma unroll
       for (int bn = 0; bn < 2; ++bn) {
         const int64_t i = i0 + wn * 64 + bn * 32 + (lane & 31);
@@ -501,7 +514,7 @@ Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused) {
   pl.off_rows = o;   o += 2 * 7 * pl.rows_stride;   // ediag, zd2, xnorm, beta, gdiag, ce, rowds
   pl.off_Xs = o;     o += 2 * align_up((size_t)d * b * 2);
   pl.off_part = o;   o += 2 * align_up((size_t)pl.splitk * b * d * 4);
-  pl.off_ymax = o;   o += 256 + align_up((size_t)2 * NORM_BLOCKS * 4);
+  pl.off_ymax = o;   o += align_up((size_t)2 * NORM_BLOCKS * 4);         // partial maxima of the row norms
   pl.total = o;
   return pl;
 }
@@ -534,8 +547,7 @@ int mfma_run(const Problem& pr, bool fused) {
   char* ws = static_cast<char*>(pr.ws);
   const uint16_t* I = static_cast<const uint16_t*>(pr.I);
   const uint16_t* T = static_cast<const uint16_t*>(pr.T);
-  float* ymax = reinterpret_cast<float*>(ws + pl.off_ymax);         // [0] = max |I_j|^2, [1] = max |T_j|^2
-  float* wgmax = ymax + 64;                                         // 2 x NORM_BLOCKS partial maxima
+  float* wgmax = reinterpret_cast<float*>(ws + pl.off_ymax);   // NORM_BLOCKS partial maxima of |I_j|^2, then of |T_j|^2
 
   Blocks bl;
   for (int z = 0; z < 2; ++z) {
@@ -554,7 +566,7 @@ int mfma_run(const Problem& pr, bool fused) {
     p.gdiag = reinterpret_cast<float*>(rows + 4 * pl.rows_stride);
     p.ce = reinterpret_cast<float*>(rows + 5 * pl.rows_stride);
     p.rowds = reinterpret_cast<float*>(rows + 6 * pl.rows_stride);
-    p.ymax2 = ymax + (z == 0 ? 1 : 0);
+    p.ymax_parts = wgmax + (z == 0 ? NORM_BLOCKS : 0);     // block A's keys are T, block C's are I
     p.Xs = reinterpret_cast<uint16_t*>(ws + pl.off_Xs + z * align_up((size_t)d * b * 2));
     p.part = reinterpret_cast<float*>(ws + pl.off_part + z * align_up((size_t)pl.splitk * b * d * 4));
     p.gq = z == 0 ? pr.gI : pr.gT;
@@ -582,8 +594,7 @@ int mfma_run(const Problem& pr, bool fused) {
   int stage = 0;
 
   stage_mark(st, stage++);
-  k_rownorm_max<<<dim3(NORM_BLOCKS, 2), 256, 0, st>>>(I, T, B, d, wgmax);
-  k_prep_diag<<<dim3((unsigned)((b + 3) / 4), 2), 256, 0, st>>>(bl, b, d, pr.rank, s2, wgmax, ymax);
+  k_prep<<<dim3((unsigned)(2 * NORM_BLOCKS + 2 * ((b + 3) / 4))), 256, 0, st>>>(bl, I, T, B, b, d, pr.rank, s2, wgmax);
   stage_mark(st, stage++);
 
   int nJp;
