@@ -129,6 +129,34 @@ DISCO_API int clip_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t
 #define DISCO_STAGES_FUSED 5
 DISCO_API int disco_set_stage_events(void** events, int count);
 
+/*
+ * Feature preparation on either side of the loss.  In Alg. 1 the encoders hand the features to the loss
+ * and take the feature gradients back; the paper prints neither the row normalisation nor the
+ * parametrisation of `t`.  Reading taken (CLIP's convention): unit-norm rows, u = x / max(|x|, 1e-12),
+ * and s = min(exp(theta), s_max).  All pointers are device pointers owned by the caller; work is enqueued
+ * on hip_stream; nothing is allocated; errors are status codes returned before anything is launched.
+ *
+ * disco_normalize_fwd: X rows x d raw features (row-major, contiguous, dtype x_dtype), U rows x d normalised
+ *   rows (dtype u_dtype: DISCO_BF16 feeds the MFMA path), inv_norm rows fp32 = 1 / max(|x|, 1e-12), kept for
+ *   the backward.  Norms and scaling in fp32; bf16 output rounded to nearest even.  X and U may be the same
+ *   buffer when the dtypes are equal.
+ * disco_normalize_bwd: G rows x d fp32 = d loss / d u (rows of gI or gT), X and inv_norm as in the forward,
+ *   DX rows x d fp32 = (G - <G, u> u) inv_norm, or G inv_norm where the 1e-12 cap was active.  DX may be G.
+ */
+DISCO_API int disco_normalize_fwd(const void* X, int64_t rows, int64_t d, int x_dtype, void* U, int u_dtype, float* inv_norm,
+                                  void* hip_stream);
+DISCO_API int disco_normalize_bwd(const float* G, const void* X, int x_dtype, const float* inv_norm, int64_t rows, int64_t d,
+                                  float* DX, void* hip_stream);
+
+/*
+ * Logit multiplier on the device: *s = min(exp(*theta), s_max) and, given *gs = d loss / d s (the gs output of
+ * the loss entry points, summed over ranks), *gtheta (+)= *gs exp(*theta) where exp(*theta) <= s_max, else 0.
+ * One fp32 each.  (The loss entry points take s by value: read *s back, or keep theta on the host.)
+ */
+DISCO_API int disco_logit_scale_fwd(const float* theta, float s_max, float* s, void* hip_stream);
+DISCO_API int disco_logit_scale_bwd(const float* theta, float s_max, const float* gs, float* gtheta, int accumulate,
+                                    void* hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 DISCO_API const char* disco_status_string(int status);
 

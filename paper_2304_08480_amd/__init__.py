@@ -18,7 +18,11 @@ from .binding import (  # noqa: F401
     DISCO_PATH_NAIVE,
     DiscoError,
     clip_loss_fwd_bwd,
+    disco_logit_scale_bwd,
+    disco_logit_scale_fwd,
     disco_loss_fwd_bwd,
+    disco_normalize_bwd,
+    disco_normalize_fwd,
     disco_resolve_path,
     disco_set_stage_events,
     disco_status_string,

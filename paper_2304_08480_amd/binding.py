@@ -50,6 +50,14 @@ def _load():
     lib.clip_loss_fwd_bwd.restype = ci
     lib.disco_set_stage_events.argtypes = [ctypes.POINTER(vp), ci]
     lib.disco_set_stage_events.restype = ci
+    lib.disco_normalize_fwd.argtypes = [vp, i64, i64, ci, vp, ci, vp, vp]
+    lib.disco_normalize_fwd.restype = ci
+    lib.disco_normalize_bwd.argtypes = [vp, vp, ci, vp, i64, i64, vp, vp]
+    lib.disco_normalize_bwd.restype = ci
+    lib.disco_logit_scale_fwd.argtypes = [vp, f32, vp, vp]
+    lib.disco_logit_scale_fwd.restype = ci
+    lib.disco_logit_scale_bwd.argtypes = [vp, f32, vp, vp, ci, vp]
+    lib.disco_logit_scale_bwd.restype = ci
     lib.disco_status_string.argtypes = [ci]
     lib.disco_status_string.restype = ctypes.c_char_p
     return lib
@@ -108,3 +116,31 @@ def clip_loss_fwd_bwd(I, T, B, d, s, dtype, path, loss, gI, gT, gs, workspace, w
 def disco_set_stage_events(events, count: int) -> int:
     """`events`: a ctypes array of c_void_p holding hipEvent_t handles (kept alive by the caller), or None."""
     return _lib.disco_set_stage_events(events, int(count))
+
+
+def disco_normalize_fwd(X, rows, d, x_dtype, U, u_dtype, inv_norm, stream=None, check=True) -> int:
+    st = _lib.disco_normalize_fwd(_ptr(X), rows, d, x_dtype, _ptr(U), u_dtype, _ptr(inv_norm), _stream_ptr(stream))
+    if check and st != DISCO_OK:
+        raise DiscoError(st, "disco_normalize_fwd")
+    return st
+
+
+def disco_normalize_bwd(G, X, x_dtype, inv_norm, rows, d, DX, stream=None, check=True) -> int:
+    st = _lib.disco_normalize_bwd(_ptr(G), _ptr(X), x_dtype, _ptr(inv_norm), rows, d, _ptr(DX), _stream_ptr(stream))
+    if check and st != DISCO_OK:
+        raise DiscoError(st, "disco_normalize_bwd")
+    return st
+
+
+def disco_logit_scale_fwd(theta, s_max, s, stream=None, check=True) -> int:
+    st = _lib.disco_logit_scale_fwd(_ptr(theta), s_max, _ptr(s), _stream_ptr(stream))
+    if check and st != DISCO_OK:
+        raise DiscoError(st, "disco_logit_scale_fwd")
+    return st
+
+
+def disco_logit_scale_bwd(theta, s_max, gs, gtheta, accumulate=0, stream=None, check=True) -> int:
+    st = _lib.disco_logit_scale_bwd(_ptr(theta), s_max, _ptr(gs), _ptr(gtheta), int(accumulate), _stream_ptr(stream))
+    if check and st != DISCO_OK:
+        raise DiscoError(st, "disco_logit_scale_bwd")
+    return st

@@ -101,3 +101,34 @@ def test_stage_events_argument_check():
 def test_auto_falls_back_to_naive_for_fp32_and_odd_shapes():
     assert dl.disco_resolve_path(256, 512, 4, dl.DISCO_F32, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
     assert dl.disco_resolve_path(300, 77, 3, dl.DISCO_BF16, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
+
+
+# ---------------------------------------------------------------- feature preparation entry points (argument checks only)
+FAKE_PTR = 0x1000
+
+
+def test_normalize_argument_checks():
+    ok = dict(X=FAKE_PTR, rows=8, d=16, x_dtype=dl.DISCO_F32, U=FAKE_PTR, u_dtype=dl.DISCO_BF16, inv=FAKE_PTR)
+
+    def fwd(**kw):
+        a = dict(ok); a.update(kw)
+        return dl.disco_normalize_fwd(a["X"], a["rows"], a["d"], a["x_dtype"], a["U"], a["u_dtype"], a["inv"], None, check=False)
+
+    assert fwd(X=None) == dl.DISCO_ERR_NULL and fwd(U=None) == dl.DISCO_ERR_NULL and fwd(inv=None) == dl.DISCO_ERR_NULL
+    assert fwd(rows=0) == dl.DISCO_ERR_SHAPE and fwd(d=-1) == dl.DISCO_ERR_SHAPE and fwd(rows=1 << 39, d=4) == dl.DISCO_ERR_SHAPE
+    assert fwd(x_dtype=5) == dl.DISCO_ERR_UNSUPPORTED and fwd(u_dtype=-1) == dl.DISCO_ERR_UNSUPPORTED
+
+    def bwd(**kw):
+        a = dict(G=FAKE_PTR, X=FAKE_PTR, x_dtype=dl.DISCO_BF16, inv=FAKE_PTR, rows=8, d=16, DX=FAKE_PTR); a.update(kw)
+        return dl.disco_normalize_bwd(a["G"], a["X"], a["x_dtype"], a["inv"], a["rows"], a["d"], a["DX"], None, check=False)
+
+    for name in ("G", "X", "inv", "DX"):
+        assert bwd(**{name: None}) == dl.DISCO_ERR_NULL
+    assert bwd(rows=0) == dl.DISCO_ERR_SHAPE and bwd(x_dtype=9) == dl.DISCO_ERR_UNSUPPORTED
+
+
+def test_logit_scale_argument_checks():
+    assert dl.disco_logit_scale_fwd(None, 100.0, FAKE_PTR, None, check=False) == dl.DISCO_ERR_NULL
+    assert dl.disco_logit_scale_fwd(FAKE_PTR, 0.0, FAKE_PTR, None, check=False) == dl.DISCO_ERR_SHAPE
+    assert dl.disco_logit_scale_bwd(FAKE_PTR, 100.0, None, FAKE_PTR, 0, None, check=False) == dl.DISCO_ERR_NULL
+    assert dl.disco_logit_scale_bwd(FAKE_PTR, float("nan"), FAKE_PTR, FAKE_PTR, 0, None, check=False) == dl.DISCO_ERR_SHAPE
