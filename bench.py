@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--path", default="auto", choices=["auto", "naive", "materialized", "fused"])
     ap.add_argument("--ranks", default="all", help="'all' (every simulated rank per step) or one rank index")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--op", default="loss", choices=["loss", "prep"],
+                    help="'loss': the hot path (default, the headline line); 'prep': the feature normalisation "
+                         "forward + backward on both feature matrices of the workload (HBM-bound, reported in GB/s)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy three times (to calibrate FETCH_SIZE / WRITE_SIZE) and exit")
     return ap.parse_args()
@@ -90,6 +93,9 @@ def main():
 
     import paper_2304_08480_amd as dl
     from synth import CONFIGS, make_config_inputs
+
+    if args.op == "prep":
+        return bench_prep(args, dl, CONFIGS[args.config], np, torch)
 
     cfg = CONFIGS[args.config]
     B, d, N, b, s = cfg.B, cfg.d, cfg.N, cfg.b, cfg.s
@@ -223,6 +229,58 @@ def main():
         "loss": float(loss.item()),
         "roofline": roofline,
         "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+def bench_prep(args, dl, cfg, np, torch):
+    """Row L2 normalisation of raw fp32 features to bf16 (forward) and the projection of the fp32 feature
+    gradients back through it (backward), for both matrices of the workload.  Algorithmic bytes per element:
+    forward 4 read + 2 written, backward 4 + 4 read + 4 written (plus 4 per row for the norms)."""
+    B, d = cfg.B, cfg.d
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device="cpu").manual_seed(cfg.seed)
+    X = [torch.randn(B, d, generator=g).mul_(2.0).to(dev) for _ in range(2)]
+    G = [torch.randn(B, d, generator=g).mul_(1e-5).to(dev) for _ in range(2)]
+    U = [torch.empty((B, d), dtype=torch.int16, device=dev) for _ in range(2)]
+    inv = [torch.empty(B, device=dev) for _ in range(2)]
+    DX = [torch.empty((B, d), device=dev) for _ in range(2)]
+    stream = torch.cuda.current_stream()
+
+    def fwd():
+        for z in range(2):
+            dl.disco_normalize_fwd(X[z], B, d, dl.DISCO_F32, U[z], dl.DISCO_BF16, inv[z], stream)
+
+    def bwd():
+        for z in range(2):
+            dl.disco_normalize_bwd(G[z], X[z], dl.DISCO_F32, inv[z], B, d, DX[z], stream)
+
+    def timed(f):
+        for _ in range(args.warmup):
+            f()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record(stream)
+        for _ in range(args.steps):
+            f()
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / args.steps
+
+    t_f, t_b = timed(fwd), timed(bwd)
+    by_f = 2 * (B * d * 6 + B * 4)
+    by_b = 2 * (B * d * 12 + B * 4)
+    gbs = (by_f + by_b) / ((t_f + t_b) * 1e-3) / 1e9
+    out = {
+        "metric": "feature normalisation fwd+bwd, both matrices", "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(t_f + t_b, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "B": B, "d": d, "in": "f32", "out": "bf16"},
+        "forward_ms": round(t_f, 4), "backward_ms": round(t_b, 4),
+        "roofline": {"bound": "hbm", "kernel": "normalize_fwd + normalize_bwd", "achieved": round(gbs, 1), "peak": 8000.0,
+                     "unit": "GB/s", "frac": round(gbs / 8000.0, 4), "traffic": None,
+                     "forward_GBps": round(by_f / (t_f * 1e-3) / 1e9, 1), "backward_GBps": round(by_b / (t_b * 1e-3) / 1e9, 1)},
+        "cpu_baseline": None,
     }
     print(json.dumps(out))
 
