@@ -208,15 +208,18 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
 // keys (nothing of size b x B is written), then STORE-only passes that recompute one panel at a time.
 template <bool STATS, bool STORE>
 __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2,
-                                                          int64_t jp0, int64_t W, int nIp, int nJp, int nblk) {
+                                                          int64_t jp0, int64_t W, int sbi, int sbj, int nblk) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  // Persistent workgroups (one per compute unit) walk the padded tile lists of the nblk blocks in bl, one after the other, with a
-  // stride of the grid size: a wave ends only when all its stores are acknowledged, so ending a workgroup
-  // per tile would expose that latency and the launch of the next workgroup 16 times per compute unit;
-  // here a tile's stores drain while the next tile's operands are fetched.  gridDim.x is a multiple of 8,
-  // so a workgroup stays on one XCD's slice of the tile list.
-  const int padded = nIp * nJp;                 // multiple of 32
-  const int chunk = padded >> 3;
+  // Persistent workgroups (one per compute unit) walk the tile lists of the nblk blocks in bl, one after the
+  // other, with a stride of the grid size: a wave ends only when all its stores are acknowledged, so ending a
+  // workgroup per tile would expose that latency and the launch of the next workgroup once per tile; here a
+  // tile's stores drain while the next tile's operands are fetched.  gridDim.x is a multiple of 8, so a
+  // workgroup stays on one XCD's contiguous eighth of the tile list.  The list runs over super-blocks of
+  // sbi query tiles x sbj key tiles (sbi divides the query tiles, sbj the key tiles, sbi sbj <= 32; 8 x 4 where
+  // the shape allows): the workgroups an XCD runs at one time then share sbi + sbj operand tiles in its L2.
+  const int nI = (int)(b / BN), nJ = (int)(W / BM);
+  const int total = nI * nJ;
+  const int chunk = (total + 7) >> 3, padded = chunk << 3;
   const int lane = threadIdx.x & 63, wn = (threadIdx.x >> 6) & 3;
   // max_j |y_j| of each block's key matrix, folded from the partial maxima (one per thread)
   float ymax_z[2];
@@ -243,12 +246,11 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
     const int u = v - z * padded;
     const BlockPtrs& p = bl.z[z];
     const int lin = (u & 7) * chunk + (u >> 3);
-    // super-blocks of 8 query tiles x 4 key tiles: 12 operand tiles (3 MiB) feed 32 concurrent workgroups
-    const int sb = lin >> 5, within = lin & 31;
-    const int nSBi = nIp >> 3;
-    const int it = (sb % nSBi) * 8 + (within & 7);
-    const int jt = (sb / nSBi) * 4 + (within >> 3);
-    if ((int64_t)it * BN >= b || (int64_t)jt * BM >= W) continue;     // padding (workgroup-uniform)
+    if ((u >> 3) >= chunk || lin >= total) continue;                  // padding of the eighths (workgroup-uniform)
+    const int sbsz = sbi * sbj, sb = lin / sbsz, within = lin % sbsz;
+    const int nSBi = nI / sbi;
+    const int it = (sb % nSBi) * sbi + within % sbi;
+    const int jt = (sb / nSBi) * sbj + within / sbi;
     const int64_t i0 = (int64_t)it * BN, j0 = jp0 + (int64_t)jt * BM;
 
     // exponent reference of this lane's two query rows, fetched before the main loop so that the loads are
@@ -578,11 +580,15 @@ int mfma_run(const Problem& pr, bool fused) {
   const float cs = c * pr.s;
   hipStream_t st = pr.stream;
   const int nI = (int)(b / BN);
-  const int nIp = (nI + 7) / 8 * 8;
-  auto logit_grid = [&](int64_t keys, int& nJp) {
+  // super-block shape of the logit tile walk: the largest power of two <= 8 dividing the query tiles, then the
+  // largest power of two dividing the key tiles that keeps the super-block within 32 tiles
+  int sbi = 8;
+  while (nI % sbi) sbi >>= 1;
+  auto logit_grid = [&](int64_t keys, int& sbj) {
     const int nJ = (int)(keys / BM);
-    nJp = (nJ + 3) / 4 * 4;
-    const int tiles2 = 2 * nIp * nJp;              // both blocks, padded (multiple of 64)
+    sbj = 32 / sbi;
+    while (nJ % sbj) sbj >>= 1;
+    const int tiles2 = 2 * ((nI * nJ + 7) / 8 * 8);     // both blocks, each padded to a multiple of 8
     return dim3((unsigned)(tiles2 < persistent_wgs ? tiles2 : persistent_wgs));
   };
   const int nMk = (int)(W / BM);
@@ -597,13 +603,13 @@ int mfma_run(const Problem& pr, bool fused) {
   k_prep<<<dim3((unsigned)(2 * NORM_BLOCKS + 2 * ((b + 3) / 4))), 256, 0, st>>>(bl, I, T, B, b, d, pr.rank, s2, wgmax);
   stage_mark(st, stage++);
 
-  int nJp;
+  int sbj;
   if (fused) {
-    const dim3 g = logit_grid(B, nJp);
-    k_logit_tiles<true, false><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, nIp, nJp, 2);
+    const dim3 g = logit_grid(B, sbj);
+    k_logit_tiles<true, false><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, sbi, sbj, 2);
   } else {
-    const dim3 g = logit_grid(B, nJp);
-    k_logit_tiles<true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, nIp, nJp, 2);
+    const dim3 g = logit_grid(B, sbj);
+    k_logit_tiles<true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, sbi, sbj, 2);
   }
   stage_mark(st, stage++);
   k_row_merge<<<dim3((unsigned)((b + 63) / 64), 2), 256, 0, st>>>(bl, b, pl.nparts);
@@ -613,8 +619,8 @@ int mfma_run(const Problem& pr, bool fused) {
   for (int pnl = 0; pnl < pl.npanels; ++pnl) {
     const int64_t jp0 = (int64_t)pnl * W;
     if (fused) {
-      const dim3 g = logit_grid(W, nJp);
-      k_logit_tiles<false, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, jp0, W, nIp, nJp, 2);
+      const dim3 g = logit_grid(W, sbj);
+      k_logit_tiles<false, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, jp0, W, sbi, sbj, 2);
     }
     if (pr.accumulate)
       k_key_grad<true><<<key_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, cs, jp0, W, nMk, pl.nN);

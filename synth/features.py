@@ -122,6 +122,10 @@ CONFIGS: Dict[str, WorkloadConfig] = {
     "b196k_n64_hard": WorkloadConfig("b196k_n64_hard", 196608, 512, 64, "bf16", 100.0, 2, noise=3.5),
     # wider embedding with 10% near-duplicate rows
     "b64k_d768_n8": WorkloadConfig("b64k_d768_n8", 65536, 768, 8, "bf16", 1.0 / 0.07, 3, hard_frac=0.10),
+    # the shape of the paper's own timing table (Table 4: 64 GPUs, batch 32,768, 512 pairs per GPU)
+    "b32k_n64": WorkloadConfig("b32k_n64", 32768, 512, 64, "bf16", 1.0 / 0.07, 1),
+    # the batch of the paper's accuracy tables (Tables 5-7: 65,536 on 64 GPUs)
+    "b64k_n64": WorkloadConfig("b64k_n64", 65536, 512, 64, "bf16", 1.0 / 0.07, 4),
 }
 
 

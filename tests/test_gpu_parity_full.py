@@ -65,7 +65,7 @@ def test_b32k_n8_ranks_dense_and_accumulated():
 
 
 @pytest.mark.parametrize("name,N,rank", [("b196k_n64", None, 37), ("b196k_n64_hard", None, 63),
-                                         ("b64k_d768_n8", None, 2)])
+                                         ("b64k_d768_n8", None, 2), ("b32k_n64", None, 41), ("b64k_n64", None, 0)])
 def test_large_workloads_sampled(name, N, rank):
     cfg, I, T, run = _setup(name, N)
     N = cfg.N if N is None else N
