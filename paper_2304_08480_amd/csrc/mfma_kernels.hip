@@ -359,8 +359,9 @@ __global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  mainloop<FMT_RB, FMT_K, true>(p.E + (jl0 >> 6) * 4096, (W >> 6) * 4096, p.Xs + k0 * b, b, (int)(b / BK), smem, acc);
-  store_tile_f32<ACCUMULATE>(acc, smem, p.gk + (jp0 + jl0) * d + k0, d, cs);
+  const int ncols = d - k0 < BN ? (int)(d - k0) : BN;              // the last column tile may be partial (d % 64 == 0)
+  mainloop<FMT_RB, FMT_K, true>(p.E + (jl0 >> 6) * 4096, (W >> 6) * 4096, p.Xs + k0 * b, b, (int)(b / BK), smem, acc, ncols);
+  store_tile_f32<ACCUMULATE>(acc, smem, p.gk + (jp0 + jl0) * d + k0, d, cs, ncols);
 }
 
 // Query-side products, split over the key index: part[ks][i][k] = sum_{j in split ks} E[i][j] y_jk.
@@ -404,9 +405,11 @@ __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  const int ncols = d - k0 < BN ? (int)(d - k0) : BN;              // the last column tile may be partial (d % 64 == 0)
   if (kts > 0)
-    mainloop<FMT_KB, FMT_R, false>(p.E + ((i0 >> 6) * (W >> 6) + kt0) * 4096, (W >> 6) * 4096, p.Yraw + (jp0 + (int64_t)kt0 * BK) * d + k0, d, kts, smem, acc);
-  store_tile_f32<ACCUMULATE>(acc, smem, p.part + (int64_t)ks * b * d + i0 * d + k0, d, 1.0f);
+    mainloop<FMT_KB, FMT_R, false>(p.E + ((i0 >> 6) * (W >> 6) + kt0) * 4096, (W >> 6) * 4096,
+                                   p.Yraw + (jp0 + (int64_t)kt0 * BK) * d + k0, d, kts, smem, acc, ncols);
+  store_tile_f32<ACCUMULATE>(acc, smem, p.part + (int64_t)ks * b * d + i0 * d + k0, d, 1.0f, ncols);
 }
 
 // Everything that lands in the rank's own rows, for both blocks at once.  With lab = label of local row i:
@@ -497,7 +500,7 @@ Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused) {
   pl.W = B / pl.npanels;
   pl.nparts = (int)(B / 128);
   pl.nMq = (int)(b / BM);
-  pl.nN = (int)(d / BN);
+  pl.nN = (int)((d + BN - 1) / BN);
   const int tiles = pl.nMq * pl.nN;
   const int kt_total = (int)(pl.W / BK);
   // split so that both blocks together give about one workgroup per compute unit (256); multiples of 4 make
@@ -645,7 +648,7 @@ bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype) {
   if (dtype != DISCO_BF16) return false;
   if (N <= 0 || B % N != 0) return false;
   const int64_t b = B / N;
-  return b % 256 == 0 && d % 256 == 0;
+  return b % 256 == 0 && d % 64 == 0;
 }
 
 size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N) { return make_plan(B, d, N, false).total; }

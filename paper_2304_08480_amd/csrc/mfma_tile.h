@@ -98,8 +98,10 @@ struct Operand {
   uint32_t lds_q;           // LDS byte offset (inside the operand tile) of the wave's first load instruction
 
   // lw: index 0..3 of this wave among the four that load this operand; row0: first tile row of this
-  // wave's fragments (multiple of 32); ld in elements
-  __device__ __forceinline__ void init(int64_t ld, int lw, int lane, int row0) {
+  // wave's fragments (multiple of 32); ld in elements; nvalid: tile rows that exist in memory (a multiple of
+  // 8, at most 256): loads of the rows past them are redirected to the last existing rows, so that they
+  // stay in bounds (the caller does not use the output rows or columns they feed)
+  __device__ __forceinline__ void init(int64_t ld, int lw, int lane, int row0, int nvalid = BM) {
     const int wave = lw;
     lds_q = NLD * wave * 1024;
 #pragma unroll
@@ -108,11 +110,13 @@ struct Operand {
       if (fmt_is_k(FMT)) {
         const int rho = 8 * q + (lane >> 3), pc = lane & 7;
         const int ch = (pc ^ ((rho >> 1) & 7)) << 3;
-        if (FMT == FMT_K) ld_off[n] = (uint32_t)(((int64_t)rho * ld + ch) * 2);
-        else ld_off[n] = (uint32_t)(((int64_t)(rho >> 6) * ld + (rho & 63) * 64 + ch) * 2);
+        const int rsrc = rho < nvalid ? rho : nvalid - 1;
+        if (FMT == FMT_K) ld_off[n] = (uint32_t)(((int64_t)rsrc * ld + ch) * 2);
+        else ld_off[n] = (uint32_t)(((int64_t)(rsrc >> 6) * ld + (rsrc & 63) * 64 + ch) * 2);
       } else {
         const int kap = 2 * q + (lane >> 5), pcw = lane & 31;
-        const int c = (((pcw >> 1) ^ ((kap & 3) << 1)) << 1) | (pcw & 1);
+        const int c0 = (((pcw >> 1) ^ ((kap & 3) << 1)) << 1) | (pcw & 1);
+        const int c = (c0 << 3) < nvalid ? c0 : (nvalid >> 3) - 1;
         if (FMT == FMT_R) ld_off[n] = (uint32_t)(((int64_t)kap * ld + (c << 3)) * 2);
         else ld_off[n] = (uint32_t)(((c >> 3) * 4096 + kap * 64 + ((c & 7) << 3)) * 2);
       }
@@ -208,7 +212,7 @@ __device__ __forceinline__ int ring_next(int u, int step) { u += step; return u 
 // READS_FIRST: issue a sub-step's LDS reads ahead of its MFMAs (otherwise the compiler places them).
 template <int FA, int FB, int GROUP, bool READS_FIRST>
 __device__ __forceinline__ void kloop(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bp, int64_t ldb,
-                                      int ktiles, char* smem, f32x16 (&acc)[4][2]) {
+                                      int ktiles, char* smem, f32x16 (&acc)[4][2], int nvalid_b) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int64_t stepA = FA == FMT_K ? BK : FA == FMT_KB ? 4096 : FA == FMT_R ? (int64_t)BK * lda : lda;
   const int64_t stepB = FB == FMT_K ? BK : FB == FMT_KB ? 4096 : FB == FMT_R ? (int64_t)BK * ldb : ldb;
@@ -216,7 +220,7 @@ __device__ __forceinline__ void kloop(const uint16_t* __restrict__ A, int64_t ld
   Operand<FA, 4> oa;
   Operand<FB, 2> ob;
   oa.init(lda, wave & 3, lane, (wave >> 2) * 128);
-  ob.init(ldb, wave & 3, lane, (wave & 3) * 64);
+  ob.init(ldb, wave & 3, lane, (wave & 3) * 64, nvalid_b);
   const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;   // LDS byte address
   const int k1 = last < 1 ? last : 1;
   if (GROUP == 0) {
@@ -279,31 +283,35 @@ __device__ __forceinline__ void kloop(const uint16_t* __restrict__ A, int64_t ld
 //   A, Bp   : element (row 0, k 0) of the workgroup's operand tiles; ktiles = K / 64 >= 1.
 //   smem    : SMEM_BYTES of LDS, 16-byte aligned; on return no load is in flight and every wave has passed
 //             a barrier, so the caller may reuse it at once.
+//   nvalid_b: rows of the B tile that exist in memory (multiple of 8, <= 256); the output columns from
+//             nvalid_b on are then meaningless and must not be stored.
 template <int FA, int FB, bool READS_FIRST>
 __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bp,
-                                         int64_t ldb, int ktiles, char* smem, f32x16 (&acc)[4][2]) {
-  if (threadIdx.x < NTHREADS / 2) kloop<FA, FB, 0, READS_FIRST>(A, lda, Bp, ldb, ktiles, smem, acc);
-  else kloop<FA, FB, 1, READS_FIRST>(A, lda, Bp, ldb, ktiles, smem, acc);
+                                         int64_t ldb, int ktiles, char* smem, f32x16 (&acc)[4][2], int nvalid_b = BN) {
+  if (threadIdx.x < NTHREADS / 2) kloop<FA, FB, 0, READS_FIRST>(A, lda, Bp, ldb, ktiles, smem, acc, nvalid_b);
+  else kloop<FA, FB, 1, READS_FIRST>(A, lda, Bp, ldb, ktiles, smem, acc, nvalid_b);
 }
 
 // Writes a workgroup's 256 x 256 fp32 accumulator tile to row-major global memory through LDS, so that
 // every global store is a full 1 KiB row segment (the accumulator layout would give 4-byte elements per
 // lane).  Two passes of 128 rows; LDS rows padded to 1056 bytes so that the two half-waves of a 4-byte
-// write land on different banks.  out points at the tile's first element; value = scale * acc (+ old).
+// write land on different banks.  out points at the tile's first element; value = scale * acc (+ old);
+// only the first ncols columns (a multiple of 4) are touched.
 constexpr int OUT_ROW_BYTES = BN * 4 + 32;
 constexpr int OUT_SMEM_BYTES = 128 * OUT_ROW_BYTES;       // 132 KiB
 
 template <bool ACCUMULATE>
-__device__ __forceinline__ void store_tile_f32(f32x16 (&acc)[4][2], char* smem, float* out, int64_t ld, float scale) {
+__device__ __forceinline__ void store_tile_f32(f32x16 (&acc)[4][2], char* smem, float* out, int64_t ld, float scale, int ncols = BN) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 2, wn = wave & 3, half = lane >> 5;
   const int chunk = t & 63, r0 = t >> 6;
+  const bool live = chunk * 4 < ncols;             // this thread's four columns exist (ncols is a multiple of 4)
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     // when accumulating, the old values are requested eight rows at a time, the first eight before the
     // staging so that their latency is paid under the LDS traffic
     f32x4 old[8];
-    if (ACCUMULATE) {
+    if (ACCUMULATE && live) {
 #pragma unroll
       for (int r = 0; r < 8; ++r) old[r] = *reinterpret_cast<const f32x4*>(out + (int64_t)(h * 128 + r * 8 + r0) * ld + chunk * 4);
     }
@@ -326,15 +334,15 @@ __device__ __forceinline__ void store_tile_f32(f32x16 (&acc)[4][2], char* smem, 
       f32x4 v[8];
 #pragma unroll
       for (int r = 0; r < 8; ++r) v[r] = *reinterpret_cast<const f32x4*>(smem + ((q * 8 + r) * 8 + r0) * OUT_ROW_BYTES + chunk * 16);
-      if (ACCUMULATE && q == 1) {
+      if (ACCUMULATE && q == 1 && live) {
 #pragma unroll
         for (int r = 0; r < 8; ++r) old[r] = *reinterpret_cast<const f32x4*>(out + (int64_t)(h * 128 + (8 + r) * 8 + r0) * ld + chunk * 4);
       }
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
         float* g = out + (int64_t)(h * 128 + (q * 8 + r) * 8 + r0) * ld + chunk * 4;
-        if (ACCUMULATE) v[r] += old[r];
-        *reinterpret_cast<f32x4*>(g) = v[r];
+        if (ACCUMULATE && live) v[r] += old[r];
+        if (live) *reinterpret_cast<f32x4*>(g) = v[r];
       }
     }
   }

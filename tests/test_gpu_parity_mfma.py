@@ -38,6 +38,9 @@ def _compare(run, ref, scale, tag):
     (1024, 256, 1, 100.0, dict(noise=3.5)),
     (2048, 256, 8, 100.0, {}),
     (512, 256, 2, 0.0, {}),
+    (1024, 320, 2, 14.285714, {}),          # feature width a multiple of 64 only: partial column tiles
+    (512, 64, 1, 14.285714, {}),
+    (1024, 640, 4, 14.285714, {}),
 ])
 @pytest.mark.parametrize("path", [dl.DISCO_PATH_MATERIALIZED, dl.DISCO_PATH_FUSED], ids=["materialized", "fused"])
 def test_mfma_path_matches_oracle(B, d, N, s, kw, path):
