@@ -30,7 +30,7 @@ PAPER_SAMPLES_PER_S = {"b32k_n64": 512 / 4.4e-3}
 
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs whose
 # summary is profiles/b32k_n8_hbm_traffic.txt (counters cannot be read from inside this process).
-MEASURED_TRAFFIC_BYTES = {("b32k_n8", "materialized", "logit_tiles"): 8.861e8}
+MEASURED_TRAFFIC_BYTES = {("b32k_n8", "materialized", "logit_tiles"): 8.857e8}
 
 
 def parse():

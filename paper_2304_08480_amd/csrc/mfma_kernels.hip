@@ -29,8 +29,8 @@ using namespace tile;
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float REF_HEADROOM = 100.f;                    // largest exponent (base 2) a stored numerator may reach
 
-constexpr int E_ROW_BYTES = BM * 2 + 16;                 // padded row of the staged numerator tile
-constexpr int E_TILE_BYTES = BN * E_ROW_BYTES;            // 132 KiB
+constexpr int E_ROW_BYTES = BM * 2;                      // row of the staged numerator tile (swizzled, not padded)
+constexpr int E_TILE_BYTES = BN * E_ROW_BYTES;            // 128 KiB
 constexpr int LOGIT_SMEM_BYTES = E_TILE_BYTES > SMEM_BYTES ? E_TILE_BYTES : SMEM_BYTES;
 constexpr int GEMM_SMEM_BYTES = OUT_SMEM_BYTES > SMEM_BYTES ? OUT_SMEM_BYTES : SMEM_BYTES;
 
@@ -148,9 +148,9 @@ __device__ __forceinline__ int64_t e_index(int64_t i, int64_t jl, int64_t W) {
 
 // Epilogue of one logit tile: numerators from the accumulators, row sums, staging of the bf16 tile in LDS.
 // The numerators leave through LDS: each lane holds 4 consecutive key columns of 32 different query rows,
-// which as direct global stores would be 16-byte fragments; staged as a row-major 256 x 256 bf16 tile (rows
-// padded to 528 bytes: conflict-free 8-byte writes and 16-byte reads) they go out as whole 512-byte row
-// segments.  DIAG: the tile contains label columns, which are stored as 0 and kept in fp32 in ediag.
+// which as direct global stores would be 16-byte fragments; staged as a row-major 256 x 256 bf16 tile (8-byte
+// granules XOR-swizzled with the row: conflict-free 8-byte writes and 16-byte reads) they go out as whole
+// 512-byte row segments.  DIAG: the tile contains label columns, which are stored as 0 and kept in fp32 in ediag.
 template <bool STATS, bool STORE, bool DIAG>
 __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)[4][2], char* smem, int64_t b, float s2, int64_t i0,
                                                int64_t j0, int64_t lab0, const float (&ref2)[2]) {
@@ -188,7 +188,9 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
           bf16x4 pk;
 #pragma unroll
           for (int r = 0; r < 4; ++r) pk[r] = (__bf16)e[r];
-          *reinterpret_cast<bf16x4*>(lrow + (jl + q * 8) * 2) = pk;
+          // 8-byte granule g of row il lives at granule g ^ (il & 31): the 32 rows of a half-wave (same g)
+          // then cover all 64 banks once
+          *reinterpret_cast<bf16x4*>(lrow + ((((jl >> 2) + q * 2) ^ (il & 31)) << 3)) = pk;
         }
       }
     }
@@ -284,7 +286,9 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
 #pragma unroll 8
       for (int r = 0; r < 16; ++r) {
         const int row = r * 16 + r0;
-        const u32x4 val = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + chunk16 * 16);
+        // undo the granule swizzle: the 16-byte chunk moved as a whole, its halves swapped in odd rows
+        const u32x4 raw = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + ((chunk16 ^ ((row & 31) >> 1)) << 4));
+        const u32x4 val = (row & 1) ? u32x4{raw[2], raw[3], raw[0], raw[1]} : raw;
         // written once, read by later kernels: streaming stores keep the operand tiles in L2
         const int64_t i = i0 + row, jl = (j0 - jp0) + chunk16 * 8;
         __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(p.E + e_index(i, jl, W)));
