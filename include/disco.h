@@ -57,7 +57,7 @@ typedef enum { DISCO_F32 = 0, DISCO_BF16 = 1 } disco_dtype;
  * DISCO_PATH_MATERIALIZED bf16 MFMA tiles.  The logit blocks are computed once; the un-normalised
  *                         softmax numerators are kept in bf16 (2*b*B*2 bytes) and feed the two
  *                         gradient contractions (12*b*B*d flop).  Needs dtype bf16, d % 64 == 0,
- *                         b % 256 == 0.
+ *                         b % 256 == 0, B <= 2^23.
  * DISCO_PATH_FUSED        bf16 MFMA tiles, streaming: a forward pass keeps the row sums on chip and
  *                         writes nothing of size b x B; the backward pass recomputes the logits one
  *                         key panel (at most 16384 keys) at a time and contracts each panel while

@@ -652,6 +652,9 @@ bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype) {
   if (dtype != DISCO_BF16) return false;
   if (N <= 0 || B % N != 0) return false;
   const int64_t b = B / N;
+  // per-lane load offsets are 32-bit byte offsets inside one operand tile: 256 rows of pitch b (Xs) or four block
+  // rows of pitch 64 W (blocked numerators) must stay below 4 GiB
+  if (B > ((int64_t)1 << 23) || b > ((int64_t)1 << 22)) return false;
   return b % 256 == 0 && d % 64 == 0;
 }
 

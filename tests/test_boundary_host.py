@@ -132,3 +132,10 @@ def test_logit_scale_argument_checks():
     assert dl.disco_logit_scale_fwd(FAKE_PTR, 0.0, FAKE_PTR, None, check=False) == dl.DISCO_ERR_SHAPE
     assert dl.disco_logit_scale_bwd(FAKE_PTR, 100.0, None, FAKE_PTR, 0, None, check=False) == dl.DISCO_ERR_NULL
     assert dl.disco_logit_scale_bwd(FAKE_PTR, float("nan"), FAKE_PTR, FAKE_PTR, 0, None, check=False) == dl.DISCO_ERR_SHAPE
+
+
+def test_mfma_paths_refuse_sizes_beyond_their_32_bit_tile_offsets():
+    big = 1 << 24
+    assert dl.disco_resolve_path(big, 512, big // 256, dl.DISCO_BF16, dl.DISCO_PATH_MATERIALIZED) == -dl.DISCO_ERR_UNSUPPORTED
+    assert dl.disco_resolve_path(big, 512, big // 256, dl.DISCO_BF16, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
+    assert dl.disco_resolve_path(1 << 23, 512, (1 << 23) // 256, dl.DISCO_BF16, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_MATERIALIZED
