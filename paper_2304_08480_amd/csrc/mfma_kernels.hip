@@ -48,7 +48,6 @@ __device__ __forceinline__ bool xcd_linear(int total, int& lin) {
 struct BlockPtrs {
   const uint16_t* X;     // b x d, the rank's rows
   const uint16_t* Y;     // B x d
-  const uint16_t* Yraw;  // same as Y
   uint16_t* E;           // b x W stored numerators of one key panel, in 64 x 64 blocks (e_index)
   float* lpart;          // (B/128) x b partial row sums (label column excluded)
   float* ediag;          // b: numerator of the label column
@@ -412,7 +411,7 @@ __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b
   const int ncols = d - k0 < BN ? (int)(d - k0) : BN;              // the last column tile may be partial (d % 64 == 0)
   if (kts > 0)
     mainloop<FMT_KB, FMT_R, false>(p.E + ((i0 >> 6) * (W >> 6) + kt0) * 4096, (W >> 6) * 4096,
-                                   p.Yraw + (jp0 + (int64_t)kt0 * BK) * d + k0, d, kts, smem, acc, ncols);
+                                   p.Y + (jp0 + (int64_t)kt0 * BK) * d + k0, d, kts, smem, acc, ncols);
   store_tile_f32<ACCUMULATE>(acc, smem, p.part + (int64_t)ks * b * d + i0 * d + k0, d, 1.0f, ncols);
 }
 
@@ -541,15 +540,12 @@ bool allow_lds(K kernel, int bytes) {
 }
 
 int mfma_run(const Problem& pr, bool fused) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    bool ok = allow_lds(k_logit_tiles<true, true>, LOGIT_SMEM_BYTES) && allow_lds(k_logit_tiles<true, false>, LOGIT_SMEM_BYTES) &&
-              allow_lds(k_logit_tiles<false, true>, LOGIT_SMEM_BYTES) && allow_lds(k_key_grad<false>, GEMM_SMEM_BYTES) &&
-              allow_lds(k_key_grad<true>, GEMM_SMEM_BYTES) && allow_lds(k_query_partial<false>, GEMM_SMEM_BYTES) &&
-              allow_lds(k_query_partial<true>, GEMM_SMEM_BYTES);
-    if (!ok) return DISCO_ERR_HIP;
-    attr_set = true;
-  }
+  // the tile kernels use more LDS than the default limit; raised once per process (one device per process here)
+  static const bool lds_ok = allow_lds(k_logit_tiles<true, true>, LOGIT_SMEM_BYTES) && allow_lds(k_logit_tiles<true, false>, LOGIT_SMEM_BYTES) &&
+                             allow_lds(k_logit_tiles<false, true>, LOGIT_SMEM_BYTES) && allow_lds(k_key_grad<false>, GEMM_SMEM_BYTES) &&
+                             allow_lds(k_key_grad<true>, GEMM_SMEM_BYTES) && allow_lds(k_query_partial<false>, GEMM_SMEM_BYTES) &&
+                             allow_lds(k_query_partial<true>, GEMM_SMEM_BYTES);
+  if (!lds_ok) return DISCO_ERR_HIP;
   const Plan pl = make_plan(pr.B, pr.d, pr.N, fused);
   const int persistent_wgs = compute_units();
   const int64_t b = pl.b, B = pl.B, d = pl.d, W = pl.W;
@@ -564,7 +560,6 @@ int mfma_run(const Problem& pr, bool fused) {
     const uint16_t* Xfull = z == 0 ? I : T;
     p.X = Xfull + (size_t)pr.rank * b * d;
     p.Y = z == 0 ? T : I;
-    p.Yraw = p.Y;
     p.E = reinterpret_cast<uint16_t*>(ws + pl.off_E + z * align_up((size_t)b * W * 2));
     p.lpart = reinterpret_cast<float*>(ws + pl.off_lpart + z * align_up((size_t)pl.nparts * b * 4));
     char* rows = ws + pl.off_rows + (size_t)z * 7 * pl.rows_stride;

@@ -81,6 +81,24 @@ def test_mfma_path_is_deterministic_and_accumulates():
     np.testing.assert_allclose(t3, t1 - 0.25, rtol=1e-6)
 
 
+def test_work_goes_to_the_stream_that_is_passed():
+    # the same call on a side stream (workspace and outputs of its own) gives the identical result, and the
+    # default stream is not involved: an event recorded on it before the call is complete at once
+    B, d, N, s = 1024, 256, 2, 14.285714
+    I, T, Ib, Tb = _inputs(B, d, 7)
+    Id, Td, dt = to_device(I, T, Ib, Tb, "bf16")
+    ref = Runner(Id, Td, B, d, N, dt, dl.DISCO_PATH_AUTO)
+    ref.rank(0, s)
+    want = ref.results()
+    side = torch.cuda.Stream()
+    run = Runner(Id, Td, B, d, N, dt, dl.DISCO_PATH_AUTO)
+    torch.cuda.synchronize()
+    dl.disco_loss_fwd_bwd(Id, Td, B, d, 0, N, s, dt, dl.DISCO_PATH_AUTO, 0, run.loss, run.gI, run.gT, run.gs, run.ws, run.ws_bytes, side)
+    side.synchronize()
+    got = (float(run.loss.item()), run.gI.cpu().numpy().astype(np.float64), run.gT.cpu().numpy().astype(np.float64), float(run.gs.item()))
+    assert got[0] == want[0] and got[3] == want[3] and np.array_equal(got[1], want[1]) and np.array_equal(got[2], want[2])
+
+
 def test_mfma_path_agrees_with_naive_path_on_gpu():
     # two independent kernel sets behind the same boundary
     B, d, N, s = 2048, 256, 4, 20.0
