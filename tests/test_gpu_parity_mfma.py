@@ -41,6 +41,9 @@ def _compare(run, ref, scale, tag):
     (1024, 320, 2, 14.285714, {}),          # feature width a multiple of 64 only: partial column tiles
     (512, 64, 1, 14.285714, {}),
     (1024, 640, 4, 14.285714, {}),
+    (3072, 192, 4, 14.285714, {}),          # 3 query tiles: super-blocks one query tile wide
+    (2560, 128, 2, 25.0, {}),               # 5 query tiles, 10 key tiles
+    (4096, 64, 16, 14.285714, {}),          # 256-pair shares
 ])
 @pytest.mark.parametrize("path", [dl.DISCO_PATH_MATERIALIZED, dl.DISCO_PATH_FUSED], ids=["materialized", "fused"])
 def test_mfma_path_matches_oracle(B, d, N, s, kw, path):
