@@ -506,13 +506,18 @@ Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused) {
   pl.nN = (int)((d + BN - 1) / BN);
   const int tiles = pl.nMq * pl.nN;
   const int kt_total = (int)(pl.W / BK);
-  // split so that both blocks together give about one workgroup per compute unit (256); multiples of 4 make
-  // the number of (block, split) slices a multiple of 8, which k_query_partial can pin to XCDs
-  int sk = (256 + 2 * tiles - 1) / (2 * tiles);
-  if (sk >= 3) sk = (sk + 1) / 4 * 4;
-  if (sk > 32) sk = 32;
-  if (sk > kt_total) sk = kt_total;
-  if (sk < 1) sk = 1;
+  // Split of the query-side reduction: the 2 * tiles * sk workgroups run in rounds of one per compute unit (256 on
+  // this chip), each taking kt_total / sk K-steps of about 1.1 us, and the sk partial tiles are written once and
+  // read once at about 4 TB/s.  Take the sk with the least estimated time.
+  int sk = 1;
+  double best = 1e300;
+  for (int c = 1; c <= 32 && c <= kt_total; ++c) {
+    const int ktps = (kt_total + c - 1) / c;
+    const int eff = (kt_total + ktps - 1) / ktps;                    // splits that are not empty
+    const int rounds = (2 * tiles * eff + 255) / 256;
+    const double cost = rounds * ktps * 1.1 + eff * (2.0 * b * d * 4.0 * 2.0) / 4e6;
+    if (cost < best) { best = cost; sk = c; }
+  }
   pl.ktps = (kt_total + sk - 1) / sk;
   pl.splitk = (kt_total + pl.ktps - 1) / pl.ktps;
   size_t o = 0;
