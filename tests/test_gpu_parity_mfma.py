@@ -137,3 +137,28 @@ def test_fused_path_needs_less_workspace_and_matches_materialized():
     assert lf == lm
     assert np.allclose(af, am, rtol=1e-4, atol=1e-10) and np.allclose(tf, tm, rtol=1e-4, atol=1e-10)
     assert gf == pytest.approx(gm, rel=1e-5)
+
+
+def test_a_rank_call_can_be_captured_in_a_graph_and_replayed():
+    # the library enqueues kernels only (no allocation, no memset, no synchronisation), so a caller may capture a
+    # call; every replay, with eager work in between, must reproduce the eager result bit for bit
+    B, d, N, s = 2048, 256, 4, 14.285714
+    I, T, Ib, Tb = _inputs(B, d, 10)
+    Id, Td, dt = to_device(I, T, Ib, Tb, "bf16")
+    eager = Runner(Id, Td, B, d, N, dt, dl.DISCO_PATH_AUTO)
+    eager.rank(1, s)
+    want = eager.results()
+    cap = Runner(Id, Td, B, d, N, dt, dl.DISCO_PATH_AUTO)
+    cap.rank(1, s)                      # warm-up outside the capture (one-time kernel attribute set-up)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cap.rank(1, s)
+    for replay in range(3):
+        cap.gI.fill_(float("nan")); cap.gT.fill_(float("nan")); cap.loss.fill_(float("nan")); cap.gs.fill_(float("nan"))
+        eager.rank(replay % N, s)       # unrelated eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        got = cap.results()
+        assert got[0] == want[0] and got[3] == want[3], f"replay {replay}"
+        assert np.array_equal(got[1], want[1]) and np.array_equal(got[2], want[2]), f"replay {replay}"
