@@ -42,6 +42,7 @@ def parse():
     ap.add_argument("--path", default="auto", choices=["auto", "naive", "materialized", "fused"])
     ap.add_argument("--ranks", default="all", help="'all' (every simulated rank per step) or one rank index")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true", help="capture one step (all rank calls) in a graph and time its replays")
     ap.add_argument("--op", default="loss", choices=["loss", "prep"],
                     help="'loss': the hot path (default, the headline line); 'prep': the feature normalisation "
                          "forward + backward on both feature matrices of the workload (HBM-bound, reported in GB/s)")
@@ -135,6 +136,16 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run_step = step
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            dl_stream = torch.cuda.current_stream()
+            for n, r in enumerate(ranks):
+                dl.disco_loss_fwd_bwd(Id, Td, B, d, r, N, s, dt, path, 1 if n > 0 else 0, loss, gI, gT, gs, ws, ws_bytes, dl_stream)
+        run_step = graph.replay
+        run_step()
+        torch.cuda.synchronize()
 
     # timed region: exactly `steps` steps, no stage events (they cost about 2 % between kernels)
     t_start = torch.cuda.Event(enable_timing=True)
@@ -143,7 +154,7 @@ def main():
     wall0 = time.perf_counter()
     t_start.record(stream)
     for k in range(args.steps):
-        step()
+        run_step()
     t_end.record(stream)
     torch.cuda.synchronize()
     wall1 = time.perf_counter()
@@ -227,6 +238,7 @@ def main():
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "B": B, "d": d, "N_simulated_ranks": N, "b": b, "s": round(s, 6),
                    "ranks_per_step": calls_per_step, "path": {1: "naive", 2: "materialized", 3: "fused"}[resolved],
+                   "launch": "graph replay" if args.graph else "eager",
                    "workspace_bytes": ws_bytes},
         "ms_per_rank_call": round(ms_per_rank, 4),
         "tflops_algorithmic": round(tflops_alg, 2),
