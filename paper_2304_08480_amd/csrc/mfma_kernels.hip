@@ -297,28 +297,30 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
   }
 }
 
-// Row totals -> beta, P_label - 1, cross-entropy.  A workgroup takes 64 rows; its 4 waves each add a
-// quarter of the column parts (lane = row, so the reads are coalesced), combined in fixed order.
-__global__ __launch_bounds__(256) void k_row_merge(Blocks bl, int64_t b, int nparts) {
-  __shared__ float red[4][64];
+// Row totals -> beta, P_label - 1, cross-entropy.  A workgroup takes 64 rows; its 16 waves each add a
+// sixteenth of the column parts (lane = row, so the reads are coalesced), combined in fixed order.
+__global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int nparts) {
+  __shared__ float red[16][64];
   const BlockPtrs& p = bl.z[blockIdx.y];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t i = (int64_t)blockIdx.x * 64 + lane;
   float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
   if (i < b) {
     int q = wave;
-    for (; q + 12 < nparts; q += 16) {
+    for (; q + 48 < nparts; q += 64) {
       a0 += p.lpart[(int64_t)q * b + i];
-      a1 += p.lpart[(int64_t)(q + 4) * b + i];
-      a2 += p.lpart[(int64_t)(q + 8) * b + i];
-      a3 += p.lpart[(int64_t)(q + 12) * b + i];
+      a1 += p.lpart[(int64_t)(q + 16) * b + i];
+      a2 += p.lpart[(int64_t)(q + 32) * b + i];
+      a3 += p.lpart[(int64_t)(q + 48) * b + i];
     }
-    for (; q < nparts; q += 4) a0 += p.lpart[(int64_t)q * b + i];
+    for (; q < nparts; q += 16) a0 += p.lpart[(int64_t)q * b + i];
   }
   red[wave][lane] = (a0 + a1) + (a2 + a3);
   __syncthreads();
   if (wave != 0 || i >= b) return;
-  const float off = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+  float off = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; w += 4) off += (red[w][lane] + red[w + 1][lane]) + (red[w + 2][lane] + red[w + 3][lane]);
   const float ed = p.ediag[i];
   const float tot = off + ed;
   p.beta[i] = 1.f / tot;
@@ -619,7 +621,7 @@ int mfma_run(const Problem& pr, bool fused) {
     k_logit_tiles<true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, sbi, sbj, 2);
   }
   stage_mark(st, stage++);
-  k_row_merge<<<dim3((unsigned)((b + 63) / 64), 2), 256, 0, st>>>(bl, b, pl.nparts);
+  k_row_merge<<<dim3((unsigned)((b + 63) / 64), 2), 1024, 0, st>>>(bl, b, pl.nparts);
   k_scale_transpose<<<dim3((unsigned)(b / 64), (unsigned)(d / 64), 2), 256, 0, st>>>(bl, b, d);
   stage_mark(st, stage++);
 
