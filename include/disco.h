@@ -25,6 +25,19 @@
  *
  * Errors are return codes.  On any status other than DISCO_OK and DISCO_ERR_HIP
  * nothing was launched and no output was touched.
+ *
+ * Stream capture: the calls enqueue kernels only (no allocation, no memset, no
+ * synchronisation), so a caller may capture them in a HIP graph.  The first call of a
+ * process on one of the bf16 MFMA paths also raises the dynamic-LDS limit of its kernels
+ * (hipFuncSetAttribute), which is not a stream operation: make one call outside any
+ * capture first.
+ *
+ * Inputs: any finite values.  The features are expected L2-normalised (what CLIP feeds
+ * the loss) and that is the fast case; rows of other norms, positives that are not the
+ * row maximum, duplicate and all-zero rows give the same results as the definition, and
+ * on the bf16 MFMA paths a row whose every logit lies more than about 110 below its
+ * Cauchy-Schwarz bound s*|x_i|*max_j|y_j| is recomputed on a slower path (its query tile of
+ * 256 rows is redone).  NaN or infinity in I, T or s propagates to the outputs.
  */
 #ifndef DISCO_H
 #define DISCO_H
@@ -41,8 +54,9 @@ extern "C" {
 typedef enum {
   DISCO_OK = 0,
   DISCO_ERR_NULL = 1,        /* a required pointer is NULL */
-  DISCO_ERR_SHAPE = 2,       /* B<=0, d<=0, N<=0, B % N != 0, rank outside [0,N), sizes beyond int32 tiles */
-  DISCO_ERR_UNSUPPORTED = 3, /* unknown dtype/path value, or the path cannot run this shape/dtype */
+  DISCO_ERR_SHAPE = 2,       /* B<=0, d<=0, N<=0, B % N != 0, rank outside [0,N), B > 2^24, d > 2^16, B/N > 2^22 */
+  DISCO_ERR_UNSUPPORTED = 3, /* unknown dtype/path value, the path cannot run this shape/dtype, or a bf16 MFMA
+                                path was handed I, T, gI or gT that is not 16-byte aligned */
   DISCO_ERR_WORKSPACE = 4,   /* workspace NULL/misaligned or smaller than disco_workspace_bytes() */
   DISCO_ERR_HIP = 5          /* a kernel launch failed; outputs are undefined */
 } disco_status;
@@ -63,7 +77,10 @@ typedef enum { DISCO_F32 = 0, DISCO_BF16 = 1 } disco_dtype;
  *                         key panel (at most 16384 keys) at a time and contracts each panel while
  *                         it is cache-resident (16*b*B*d flop, workspace 2*b*W*2 bytes for panel
  *                         width W).  Same shape limits as MATERIALIZED.
- * DISCO_PATH_AUTO         the fastest path that supports the arguments.
+ * DISCO_PATH_AUTO         the fastest path that supports the arguments: MATERIALIZED when its shape
+ *                         limits hold, else NAIVE.  Shares that are not a multiple of 256 pairs, feature
+ *                         widths that are not a multiple of 64 and fp32 inputs therefore run on the vector
+ *                         ALUs, an order of magnitude slower; disco_resolve_path tells which path a call takes.
  */
 typedef enum {
   DISCO_PATH_AUTO = 0,
@@ -84,7 +101,8 @@ DISCO_API size_t disco_workspace_bytes(int64_t B, int64_t d, int32_t N, int dtyp
  * One rank's forward + backward (Alg. 1 lines "scaled dot product similarities" to
  * "loss backward"; Sec. 4.1 Eq. 4-6).
  *
- *   I, T        device, row-major B x d, contiguous, dtype `dtype` (bf16 = raw 16-bit patterns).
+ *   I, T        device, row-major B x d, contiguous, dtype `dtype` (bf16 = raw 16-bit patterns),
+ *               16-byte aligned for the bf16 MFMA paths (as gI and gT).
  *               Expected L2-normalised by the caller; gradients are w.r.t. the arrays as given.
  *   B, d        global batch and feature width.   rank, N: 0 <= rank < N, B % N == 0.
  *   s           logit multiplier (1/temperature).
@@ -111,8 +129,9 @@ DISCO_API int clip_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t
 /*
  * Stage timing for benchmarks (measurement only; the paper reports per-operator times in Table 4).
  * `events` is a caller-owned array of `count` hipEvent_t handles (created with timing enabled), or
- * NULL to switch stage timing off (the default).  While set, every disco_loss_fwd_bwd /
- * clip_loss_fwd_bwd call made from any thread records events[0] on its stream before its first
+ * NULL to switch stage timing off (the default).  The setting is process-wide: it is meant for a
+ * benchmark that owns the process, not for use next to other callers of the library.  While set, every
+ * disco_loss_fwd_bwd / clip_loss_fwd_bwd call made from any thread records events[0] on its stream before its first
  * kernel and events[k] after stage k, for as many stages as fit in `count`; the caller synchronises
  * and reads the intervals with hipEventElapsedTime.  The library keeps the pointer until it is
  * replaced.  Stages of DISCO_PATH_MATERIALIZED (DISCO_STAGES_MATERIALIZED = 6):

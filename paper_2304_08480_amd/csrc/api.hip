@@ -32,8 +32,13 @@ int check_shape(int64_t B, int64_t d, int32_t N) {
   if (B % N != 0) return DISCO_ERR_SHAPE;
   // tile indices and row offsets are kept in 32-bit registers inside the kernels
   if (B > (int64_t)1 << 24 || d > (int64_t)1 << 16) return DISCO_ERR_SHAPE;
+  // the fp32 path walks the rank's rows in 64-row tiles along a grid dimension limited to 65535 workgroups
+  if (B / N > (int64_t)1 << 22) return DISCO_ERR_SHAPE;
   return DISCO_OK;
 }
+
+// 16-byte alignment of the feature matrices: the bf16 tile kernels fetch them in 16-byte pieces
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int resolve(int64_t B, int64_t d, int32_t N, int dtype, int path) {
   int st = check_shape(B, d, N);
@@ -79,6 +84,7 @@ extern "C" int disco_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64
                                                : mfma_fused_workspace_bytes(B, d, N);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < need)
     return DISCO_ERR_WORKSPACE;
+  if (r != DISCO_PATH_NAIVE && !(aligned16(I) && aligned16(T) && aligned16(gI) && aligned16(gT))) return DISCO_ERR_UNSUPPORTED;
 
   Problem p;
   p.I = I; p.T = T; p.B = B; p.d = d; p.rank = rank; p.N = N; p.b = B / N; p.s = s; p.dtype = dtype;
@@ -102,8 +108,8 @@ extern "C" const char* disco_status_string(int status) {
     case DISCO_OK: return "ok";
     case DISCO_ERR_NULL: return "a required pointer is NULL";
     case DISCO_ERR_SHAPE: return "invalid shape: need B, d, N > 0, B % N == 0, 0 <= rank < N";
-    case DISCO_ERR_UNSUPPORTED: return "dtype/path value unknown or path does not support this shape and dtype";
-    case DISCO_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or smaller than disco_workspace_bytes()";
+    case DISCO_ERR_UNSUPPORTED: return "dtype/path value unknown, path does not support this shape and dtype, or a bf16 MFMA path was given a matrix that is not 16-byte aligned";
+    case DISCO_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or smaller than disco_workspace_bytes() (static entry point: the call needs more than disco_static_scratch_bytes())";
     case DISCO_ERR_HIP: return "a HIP kernel launch failed";
     default: return "unknown status";
   }

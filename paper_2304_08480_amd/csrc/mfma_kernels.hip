@@ -13,7 +13,11 @@
 //   query-side gradient  gX_i = c s [ beta_i (E Y)_i + (P_i,label - 1) y_label ]
 //   key-side gradient    gY_j = c s [ sum_i E_ij beta_i x_i  (+ (P_i,label - 1) x_i  if j = label_i) ]
 //   d/ds share           c <gX_i / (c s), x_i>  summed over i   (sum_ij G_ij S_ij = <G Y, X>)
-// Since lse_i >= z_i,label, every E_ij that underflows is negligible against the row total.
+// Since lse_i >= z_i,label, every E_ij that underflows is negligible against the row total.  Where the guard
+// lifts ref2_i so far above every logit of the row that the row total itself falls below 2^-60 (rows of large
+// norm whose cosines are all small, positives far below the Cauchy-Schwarz bound), k_row_merge flags the row's
+// query tile and k_logit_repair redoes that tile with the true row maximum as its reference (a slow path for
+// inputs that are not CLIP-like; it returns at once when nothing is flagged).
 //
 // One 256x256x64 NT tile main loop (mfma_tile.h: 8 waves, each 128x64 = 4x2 MFMA 32x32x16 blocks, operands
 // loaded global -> LDS directly into a ring of five units) serves all three contractions; operands whose
@@ -53,6 +57,8 @@ struct BlockPtrs {
   float* ediag;          // b: numerator of the label column
   float* zd2;            // b: z2 of the positive pair
   float* xnorm;          // b: |x_i|
+  float* ref2;           // b: exponent reference of the row (written by the statistics pass, replaced by a repair)
+  int* tileflag;         // b / 256: set when a row of that query tile has lost its row total to underflow
   const float* ymax_parts; // NORM_BLOCKS partial maxima of |y_j|^2
   float* beta;           // b
   float* gdiag;          // b: P_label - 1
@@ -81,7 +87,8 @@ static_assert(NORM_BLOCKS == NTHREADS, "the logit kernel folds the partial maxim
 //    for the overflow guard, to wgmax[which * NORM_BLOCKS + index].  A wave takes 8 rows at a time (one 16-byte
 //    load per lane and row in flight, d is a multiple of 8) and reduces the 8 row sums with interleaved
 //    butterflies.  No atomics: the consumers fold the partial maxima (max is exact, so order does not matter).
-//  * the rest: positive-pair logit and query norm of every local row, one wave per (block, row).
+//  * the rest: positive-pair logit and query norm of every local row, one wave per (block, row); the first of
+//    these workgroups also clears the query-tile repair flags of both blocks.
 __global__ __launch_bounds__(256) void k_prep(Blocks bl, const uint16_t* I, const uint16_t* T, int64_t B, int64_t b, int64_t d, int rank,
                                               float s2, float* wgmax) {
   __shared__ float red[4];
@@ -123,6 +130,8 @@ __global__ __launch_bounds__(256) void k_prep(Blocks bl, const uint16_t* I, cons
   }
   const int64_t rb = (b + 3) / 4;                       // row workgroups per block
   const int64_t q = (int64_t)blockIdx.x - 2 * NORM_BLOCKS;
+  if (q == 0)
+    for (int64_t it = threadIdx.x; it < b / BN; it += 256) { bl.z[0].tileflag[it] = 0; bl.z[1].tileflag[it] = 0; }
   const BlockPtrs& p = bl.z[q / rb];
   const int64_t i = (q % rb) * 4 + wave;
   if (i >= b) return;
@@ -150,9 +159,12 @@ __device__ __forceinline__ int64_t e_index(int64_t i, int64_t jl, int64_t W) {
 // which as direct global stores would be 16-byte fragments; staged as a row-major 256 x 256 bf16 tile (8-byte
 // granules XOR-swizzled with the row: conflict-free 8-byte writes and 16-byte reads) they go out as whole
 // 512-byte row segments.  DIAG: the tile contains label columns, which are stored as 0 and kept in fp32 in ediag.
-template <bool STATS, bool STORE, bool DIAG>
+// LOCAL (with STATS): the row sums and the label numerators are added into rs / kept in ed (registers of the
+// lane, indexed like ref2) instead of being written to lpart / ediag.
+template <bool STATS, bool STORE, bool DIAG, bool LOCAL = false>
 __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)[4][2], char* smem, int64_t b, float s2, int64_t i0,
-                                               int64_t j0, int64_t lab0, const float (&ref2)[2]) {
+                                               int64_t j0, int64_t lab0, const float (&ref2)[2], float* rs = nullptr,
+                                               float* ed = nullptr) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3, half = lane >> 5;
 #pragma unroll
@@ -178,7 +190,8 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
 #pragma unroll
           for (int r = 0; r < 4; ++r)
             if (dl == bm * 32 + q * 8 + r) {
-              if (STATS) p.ediag[i] = e[r];
+              if (STATS && LOCAL) ed[bn] = e[r];
+              else if (STATS) p.ediag[i] = e[r];
               e[r] = 0.f;
             }
         }
@@ -193,11 +206,33 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
         }
       }
     }
-    if (STATS) {
+    if (STATS && LOCAL) {
+      rs[bn] += rowsum;
+    } else if (STATS) {
       rowsum += __shfl_xor(rowsum, 32);
       if (half == 0) p.lpart[((j0 >> 7) + wm) * b + i] = rowsum;
     }
   }
+}
+
+// Copies the staged 256 x 256 bf16 numerator tile (see logit_epilogue) from LDS to the blocked E panel of
+// width W; jl0 = first key column of the tile relative to the panel.  Barriers on both sides: every wave has
+// staged its part before the copy, and the staged tile has been read before the next tile loads into LDS.
+__device__ __forceinline__ void store_staged_numerators(const BlockPtrs& p, const char* smem, int64_t i0, int64_t jl0, int64_t W) {
+  lds_barrier();
+  const int t = threadIdx.x;
+  const int chunk16 = t & 31, r0 = t >> 5;   // 32 chunks of 16 bytes per 512-byte row; 16 rows per pass
+#pragma unroll 8
+  for (int r = 0; r < 16; ++r) {
+    const int row = r * 16 + r0;
+    // undo the granule swizzle: the 16-byte chunk moved as a whole, its halves swapped in odd rows
+    const u32x4 raw = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + ((chunk16 ^ ((row & 31) >> 1)) << 4));
+    const u32x4 val = (row & 1) ? u32x4{raw[2], raw[3], raw[0], raw[1]} : raw;
+    // written once, read by later kernels: streaming stores keep the operand tiles in L2
+    const int64_t i = i0 + row, jl = jl0 + chunk16 * 8;
+    __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(p.E + e_index(i, jl, W)));
+  }
+  lds_barrier();
 }
 
 // Logit tile + softmax numerators for the key panel [jp0, jp0 + W).  Tile rows (MFMA M side) are key rows
@@ -207,6 +242,8 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
 //   STORE: write the bf16 numerators to E (panel-relative columns, 64 x 64 blocked storage, see e_index).
 // materialized path: STATS and STORE, one panel = all keys.  fused path: a STATS-only pass over all
 // keys (nothing of size b x B is written), then STORE-only passes that recompute one panel at a time.
+// A STATS pass derives the rows' exponent references and records them in ref2 (first key tile); a pass without
+// STATS reads them from there, so that it sees the references a repair has replaced.
 template <bool STATS, bool STORE>
 __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2,
                                                           int64_t jp0, int64_t W, int sbi, int sbj, int nblk) {
@@ -262,7 +299,12 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
 #pragma unroll
       for (int bn = 0; bn < 2; ++bn) {
         const int64_t i = i0 + wn * 64 + bn * 32 + (lane & 31);
-        ref2[bn] = fmaxf(p.zd2[i], fabsf(s2) * p.xnorm[i] * ymax - REF_HEADROOM);
+        if (STATS) {
+          ref2[bn] = fmaxf(p.zd2[i], fabsf(s2) * p.xnorm[i] * ymax - REF_HEADROOM);
+          if (jt == 0 && threadIdx.x < NTHREADS / 2 && lane < 32) p.ref2[i] = ref2[bn];
+        } else {
+          ref2[bn] = p.ref2[i];
+        }
       }
     }
     f32x16 acc[4][2];
@@ -278,23 +320,20 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
     // Only the tiles that the label diagonal crosses pay for finding the label column.
     if ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) logit_epilogue<STATS, STORE, true>(p, acc, smem, b, s2, i0, j0, lab0, ref2);
     else logit_epilogue<STATS, STORE, false>(p, acc, smem, b, s2, i0, j0, lab0, ref2);
-    if (STORE) {
-      lds_barrier();
-      const int t = threadIdx.x;
-      const int chunk16 = t & 31, r0 = t >> 5;   // 32 chunks of 16 bytes per 512-byte row; 16 rows per pass
-#pragma unroll 8
-      for (int r = 0; r < 16; ++r) {
-        const int row = r * 16 + r0;
-        // undo the granule swizzle: the 16-byte chunk moved as a whole, its halves swapped in odd rows
-        const u32x4 raw = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + ((chunk16 ^ ((row & 31) >> 1)) << 4));
-        const u32x4 val = (row & 1) ? u32x4{raw[2], raw[3], raw[0], raw[1]} : raw;
-        // written once, read by later kernels: streaming stores keep the operand tiles in L2
-        const int64_t i = i0 + row, jl = (j0 - jp0) + chunk16 * 8;
-        __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(p.E + e_index(i, jl, W)));
-      }
-      lds_barrier();                             // the staged tile has been read: the next tile may load into LDS
-    }
+    if (STORE) store_staged_numerators(p, smem, i0, j0 - jp0, W);
   }
+}
+
+constexpr float LN2 = 0.6931471805599453f;
+constexpr float ROW_TOTAL_FLOOR = 0x1p-60f;
+
+// beta, P_label - 1 and the cross-entropy of row i from its off-label sum, its label numerator and their total.
+// ce = log(tot / ed); when the label numerator does not dominate it is taken from the exponents,
+// log(tot) - (z2_label - ref2) ln 2, which stays finite when ed itself has underflowed.
+__device__ __forceinline__ void row_outputs(const BlockPtrs& p, int64_t i, float off, float ed, float tot) {
+  p.beta[i] = 1.f / tot;
+  p.gdiag[i] = -off / tot;
+  p.ce[i] = (ed > 0.5f * tot) ? log1pf(off / ed) : logf(tot) - (p.zd2[i] - p.ref2[i]) * LN2;
 }
 
 // Row totals -> beta, P_label - 1, cross-entropy.  A workgroup takes 64 rows; its 16 waves each add a
@@ -323,9 +362,93 @@ __global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int np
   for (int w = 0; w < 16; w += 4) off += (red[w][lane] + red[w + 1][lane]) + (red[w + 2][lane] + red[w + 3][lane]);
   const float ed = p.ediag[i];
   const float tot = off + ed;
-  p.beta[i] = 1.f / tot;
-  p.gdiag[i] = -off / tot;
-  p.ce[i] = (ed > 0.5f * tot) ? log1pf(off / ed) : logf(tot) - logf(ed);
+  row_outputs(p, i, off, ed, tot);
+  // The guard lifted the reference so far above every logit of this row that its total is (next to) lost:
+  // the row's query tile is redone against the true row maximum.  Also catches non-finite totals.
+  if (!(tot >= ROW_TOTAL_FLOOR)) p.tileflag[i >> 8] = 1;
+}
+
+// The statistics kernels of a flagged query tile, redone by one workgroup per (block, query tile): a first
+// sweep over all keys finds every row's true maximum logit, which becomes its exponent reference (ref2), a
+// second sweep forms the numerators (stored to E when STORE) and the row sums against it, and the rows'
+// beta, P_label - 1 and cross-entropy are written directly.  Workgroups of tiles that are not flagged return
+// at once, which is the normal case: the kernel then costs one launch.
+template <bool STORE>
+__global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int nI = (int)(b / BN), nJ = (int)(B / BM);
+  const int z = blockIdx.x / nI, it = blockIdx.x % nI;
+  const BlockPtrs& p = bl.z[z];
+  if (p.tileflag[it] == 0) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3, half = lane >> 5;
+  const int64_t i0 = (int64_t)it * BN, lab0 = (int64_t)rank * b;
+  float* red = reinterpret_cast<float*>(smem);            // [2][256] exchange between the two key halves
+  f32x16 acc[4][2];
+  float ref2[2] = {-INFINITY, -INFINITY};
+  for (int jt = 0; jt < nJ; ++jt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    mainloop<FMT_K, FMT_K, true>(p.Y + (int64_t)jt * BM * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
+#pragma unroll
+    for (int bn = 0; bn < 2; ++bn)
+#pragma unroll
+      for (int bm = 0; bm < 4; ++bm)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) ref2[bn] = fmaxf(ref2[bn], acc[bm][bn][e] * s2);
+  }
+#pragma unroll
+  for (int bn = 0; bn < 2; ++bn) {
+    ref2[bn] = fmaxf(ref2[bn], __shfl_xor(ref2[bn], 32));
+    if (half == 0) red[wm * 256 + wn * 64 + bn * 32 + lane] = ref2[bn];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int bn = 0; bn < 2; ++bn) {
+    const int il = wn * 64 + bn * 32 + (lane & 31);
+    ref2[bn] = fmaxf(red[il], red[256 + il]);
+    if (wm == 0 && half == 0) p.ref2[i0 + il] = ref2[bn];
+  }
+  __syncthreads();                                         // red is read before the main loop reuses the LDS
+
+  float rs[2] = {0.f, 0.f}, ed[2] = {0.f, 0.f};
+  for (int jt = 0; jt < nJ; ++jt) {
+    const int64_t j0 = (int64_t)jt * BM;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
+    if ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) logit_epilogue<true, STORE, true, true>(p, acc, smem, b, s2, i0, j0, lab0, ref2, rs, ed);
+    else logit_epilogue<true, STORE, false, true>(p, acc, smem, b, s2, i0, j0, lab0, ref2, rs, ed);
+    if (STORE) store_staged_numerators(p, smem, i0, j0, B);
+  }
+  // row totals: the four lanes (two key halves x two lane halves) that share a row; exactly one of them met the label
+  __syncthreads();
+#pragma unroll
+  for (int bn = 0; bn < 2; ++bn) {
+    rs[bn] += __shfl_xor(rs[bn], 32);
+    ed[bn] += __shfl_xor(ed[bn], 32);
+    if (half == 0) {
+      red[wm * 256 + wn * 64 + bn * 32 + lane] = rs[bn];
+      red[512 + wm * 256 + wn * 64 + bn * 32 + lane] = ed[bn];
+    }
+  }
+  __syncthreads();
+  if (wm == 0 && half == 0) {
+#pragma unroll
+    for (int bn = 0; bn < 2; ++bn) {
+      const int il = wn * 64 + bn * 32 + lane;
+      const float off = red[il] + red[256 + il], e = red[512 + il] + red[768 + il];
+      p.ediag[i0 + il] = e;
+      row_outputs(p, i0 + il, off, e, off + e);
+    }
+  }
 }
 
 // Xs[k][i] = bf16(beta_i * x_ik): the key-side contraction's right operand with the reduction index contiguous.
@@ -479,13 +602,15 @@ __global__ __launch_bounds__(1024) void k_scalars(Blocks bl, int64_t b, float c,
   }
 }
 
+constexpr int NROWARRAYS = 8;
+
 struct Plan {
   int64_t b, B, d;
   int64_t W;             // key panel width (B for the materialized path)
   int npanels;
   int nparts;            // B / 128
   int nMq, nN, splitk, ktps;
-  size_t off_E, off_lpart, off_rows, off_Xs, off_part, off_ymax, total;
+  size_t off_E, off_lpart, off_rows, off_Xs, off_part, off_ymax, off_flags, total;
   size_t rows_stride;    // bytes of one b-float row array (aligned)
 };
 
@@ -526,10 +651,11 @@ Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused) {
   pl.off_E = o;      o += 2 * align_up((size_t)b * pl.W * 2);
   pl.off_lpart = o;  o += 2 * align_up((size_t)pl.nparts * b * 4);
   pl.rows_stride = align_up((size_t)b * 4);
-  pl.off_rows = o;   o += 2 * 7 * pl.rows_stride;   // ediag, zd2, xnorm, beta, gdiag, ce, rowds
+  pl.off_rows = o;   o += 2 * NROWARRAYS * pl.rows_stride;   // ediag, zd2, xnorm, beta, gdiag, ce, rowds, ref2
   pl.off_Xs = o;     o += 2 * align_up((size_t)d * b * 2);
   pl.off_part = o;   o += 2 * align_up((size_t)pl.splitk * b * d * 4);
   pl.off_ymax = o;   o += align_up((size_t)2 * NORM_BLOCKS * 4);         // partial maxima of the row norms
+  pl.off_flags = o;  o += 2 * align_up((size_t)(b / BN) * 4);            // repair flags, one per query tile
   pl.total = o;
   return pl;
 }
@@ -549,7 +675,8 @@ bool allow_lds(K kernel, int bytes) {
 int mfma_run(const Problem& pr, bool fused) {
   // the tile kernels use more LDS than the default limit; raised once per process (one device per process here)
   static const bool lds_ok = allow_lds(k_logit_tiles<true, true>, LOGIT_SMEM_BYTES) && allow_lds(k_logit_tiles<true, false>, LOGIT_SMEM_BYTES) &&
-                             allow_lds(k_logit_tiles<false, true>, LOGIT_SMEM_BYTES) && allow_lds(k_key_grad<false>, GEMM_SMEM_BYTES) &&
+                             allow_lds(k_logit_tiles<false, true>, LOGIT_SMEM_BYTES) && allow_lds(k_logit_repair<false>, LOGIT_SMEM_BYTES) &&
+                             allow_lds(k_logit_repair<true>, LOGIT_SMEM_BYTES) && allow_lds(k_key_grad<false>, GEMM_SMEM_BYTES) &&
                              allow_lds(k_key_grad<true>, GEMM_SMEM_BYTES) && allow_lds(k_query_partial<false>, GEMM_SMEM_BYTES) &&
                              allow_lds(k_query_partial<true>, GEMM_SMEM_BYTES);
   if (!lds_ok) return DISCO_ERR_HIP;
@@ -569,7 +696,7 @@ int mfma_run(const Problem& pr, bool fused) {
     p.Y = z == 0 ? T : I;
     p.E = reinterpret_cast<uint16_t*>(ws + pl.off_E + z * align_up((size_t)b * W * 2));
     p.lpart = reinterpret_cast<float*>(ws + pl.off_lpart + z * align_up((size_t)pl.nparts * b * 4));
-    char* rows = ws + pl.off_rows + (size_t)z * 7 * pl.rows_stride;
+    char* rows = ws + pl.off_rows + (size_t)z * NROWARRAYS * pl.rows_stride;
     p.ediag = reinterpret_cast<float*>(rows + 0 * pl.rows_stride);
     p.zd2 = reinterpret_cast<float*>(rows + 1 * pl.rows_stride);
     p.xnorm = reinterpret_cast<float*>(rows + 2 * pl.rows_stride);
@@ -577,6 +704,8 @@ int mfma_run(const Problem& pr, bool fused) {
     p.gdiag = reinterpret_cast<float*>(rows + 4 * pl.rows_stride);
     p.ce = reinterpret_cast<float*>(rows + 5 * pl.rows_stride);
     p.rowds = reinterpret_cast<float*>(rows + 6 * pl.rows_stride);
+    p.ref2 = reinterpret_cast<float*>(rows + 7 * pl.rows_stride);
+    p.tileflag = reinterpret_cast<int*>(ws + pl.off_flags + z * align_up((size_t)(b / BN) * 4));
     p.ymax_parts = wgmax + (z == 0 ? NORM_BLOCKS : 0);     // block A's keys are T, block C's are I
     p.Xs = reinterpret_cast<uint16_t*>(ws + pl.off_Xs + z * align_up((size_t)d * b * 2));
     p.part = reinterpret_cast<float*>(ws + pl.off_part + z * align_up((size_t)pl.splitk * b * d * 4));
@@ -622,6 +751,8 @@ int mfma_run(const Problem& pr, bool fused) {
   }
   stage_mark(st, stage++);
   k_row_merge<<<dim3((unsigned)((b + 63) / 64), 2), 1024, 0, st>>>(bl, b, pl.nparts);
+  if (fused) k_logit_repair<false><<<dim3((unsigned)(2 * nI)), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2);
+  else k_logit_repair<true><<<dim3((unsigned)(2 * nI)), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2);
   k_scale_transpose<<<dim3((unsigned)(b / 64), (unsigned)(d / 64), 2), 256, 0, st>>>(bl, b, d);
   stage_mark(st, stage++);
 

@@ -167,7 +167,8 @@ __global__ __launch_bounds__(256) void naive_key_grad(const void* I, const void*
   const int z = blockIdx.z;
   BlockView v = block_view(I, T, dtype, b, B, d, rank, ws, z);
   float* out = z == 0 ? gT : gI;
-  int64_t m0 = (int64_t)blockIdx.y * TS, n0 = (int64_t)blockIdx.x * TS;
+  // the B key rows run along grid.x (up to 2^31 - 1 workgroups), the feature columns along grid.y
+  int64_t m0 = (int64_t)blockIdx.x * TS, n0 = (int64_t)blockIdx.y * TS;
   tile_product(
       B, d, b, m0, n0, [&](int64_t m, int64_t k) { return v.W[k * B + m]; },
       [&](int64_t k, int64_t n) { return load_feat(v.X, dtype, k * d + n); },
@@ -220,7 +221,7 @@ int naive_run(const Problem& p) {
   stage_mark(p.stream, 2);
   naive_scalars<<<1, 256, 0, p.stream>>>(row_ce, row_ds, 2 * b, c, p.accumulate, p.loss, p.gs);
   stage_mark(p.stream, 3);
-  naive_key_grad<<<dim3(cdiv(d, TS), cdiv(B, TS), 2), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,
+  naive_key_grad<<<dim3(cdiv(B, TS), cdiv(d, TS), 2), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,
                                                                           p.accumulate, p.gI, p.gT);
   stage_mark(p.stream, 4);
   naive_query_grad<<<dim3(cdiv(d, TS), cdiv(b, TS), 2), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,

@@ -92,6 +92,48 @@ def clip_pairs(B: int, d: int, seed: int, *, noise: float = 0.5,
     return I, T
 
 
+ADVERSARIAL_KINDS = ("norms", "permuted", "anti", "duplicates", "zero_rows", "big_norm_low_cos")
+
+
+def adversarial_pairs(B: int, d: int, seed: int, kind: str, block: int = 256) -> Tuple[np.ndarray, np.ndarray]:
+    """Feature pairs that are NOT CLIP-like, as float32: inputs a loss implementation must still get right.
+
+    All start from clip_pairs(B, d, seed) (positive cosine about 0.894) and then
+      norms            rows of I and T scaled by independent factors drawn uniformly from [0.3, 3]
+      permuted         the text rows of every other block of `block` pairs rotated by one inside the block:
+                       the positive pair of those rows is a random pair, its true partner (cosine 0.894)
+                       sits next to it as a negative
+      anti             every third text row negated: positives with cosine about -0.894
+      duplicates       every 16th pair overwritten by a copy of the pair 5 places before it (both matrices):
+                       exact duplicate keys, and negatives that tie with the positive
+      zero_rows        one image row and a different text row set to zero
+      big_norm_low_cos weak positives (noise 3.5: cosine about 0.27), every row scaled to norm 4
+    """
+    if kind not in ADVERSARIAL_KINDS:
+        raise ValueError(f"unknown kind {kind}")
+    rng = np.random.default_rng(seed + 1000)
+    I, T = clip_pairs(B, d, seed, noise=3.5 if kind == "big_norm_low_cos" else 0.5)
+    if kind == "norms":
+        I = I * rng.uniform(0.3, 3.0, size=(B, 1)).astype(np.float32)
+        T = T * rng.uniform(0.3, 3.0, size=(B, 1)).astype(np.float32)
+    elif kind == "permuted":
+        for lo in range(0, B, 2 * block):
+            hi = min(B, lo + block)
+            T[lo:hi] = np.roll(T[lo:hi], 1, axis=0)
+    elif kind == "anti":
+        T[::3] = -T[::3]
+    elif kind == "duplicates":
+        idx = np.arange(5, B, 16)
+        I[idx] = I[idx - 5]
+        T[idx] = T[idx - 5]
+    elif kind == "zero_rows":
+        I[B // 3] = 0.0
+        T[(2 * B) // 3 + 1] = 0.0
+    elif kind == "big_norm_low_cos":
+        I, T = 4.0 * I, 4.0 * T
+    return np.ascontiguousarray(I, dtype=np.float32), np.ascontiguousarray(T, dtype=np.float32)
+
+
 @dataclass(frozen=True)
 class WorkloadConfig:
     name: str

@@ -52,17 +52,20 @@ class Runner:
 # Scalars (loss, d/ds) and the Frobenius-relative error of each gradient tensor use the stated bars:
 # 1e-4 for fp32 inputs, 2e-2 for bf16 inputs with fp32 accumulation.  (The loss never sees a bf16
 # rounding, its row sums are fp32, so it keeps 1e-4 in both; d/ds gets ten times the loss bar.)
-# The stated absolute floor for bf16 gradients, 1e-3, is larger than any gradient entry (they are of
-# size 1/(2B) and below), so it is asserted but decides nothing.  The elementwise bound that does
-# decide is derived from the arithmetic: every gradient entry is a sum of products, and on the bf16
-# path each factor of each product is rounded to bf16 once (8 significant bits, unit roundoff u = 2^-8), so
-#     |error_ik| <= 2u * sum_j |term_ijk|  (1 + o(1))
-# whatever cancels in the sum.  The sum of term magnitudes comes from the oracle
-# (disco_rank_term_scale); k = 2u with 10% slack = 8.6e-3.  On the fp32 path the same sum bounds the
-# accumulation error: k = 1e-5 (about 2^-24 * sqrt(terms) with slack) next to the stated 1e-4 * |ref|.
+# Elementwise, TWO bounds are asserted and every entry must meet the smaller one:
+#  (stated)  |error| <= abs * max|ref| + rel * |ref|, the stated bar with its absolute part taken relative to
+#            the tensor's largest magnitude (a literal 1e-3 would exceed every gradient entry, which are of size
+#            1/(2B) and below): rel 2e-2, abs 1e-3 for bf16; rel 1e-4, abs 1e-5 for fp32 (sequential fp32
+#            accumulation of B terms alone gives about sqrt(B) * 2^-24 = 1e-6 of the largest entries);
+#  (derived) every gradient entry is a sum of products, and on the bf16 path each factor of each product is
+#            rounded to bf16 once (8 significant bits, unit roundoff u = 2^-8), so
+#                |error_ik| <= 2u * sum_j |term_ijk|  (1 + o(1))
+#            whatever cancels in the sum.  The sum of term magnitudes comes from the oracle
+#            (disco_rank_term_scale); k = 2u with 10% slack = 8.6e-3.  On the fp32 path the same sum bounds the
+#            accumulation error: k = 1e-5 (about 2^-24 * sqrt(terms) with slack) next to 1e-4 * |ref|.
 TOL = {
-    "f32": dict(scalar=1e-4, frob=1e-4, rel=1e-4, k_scale=1e-5),
-    "bf16": dict(scalar=1e-4, frob=2e-2, rel=0.0, k_scale=8.6e-3),
+    "f32": dict(scalar=1e-4, frob=1e-4, rel=1e-4, k_scale=1e-5, stated_abs=1e-5, stated_rel=1e-4),
+    "bf16": dict(scalar=1e-4, frob=2e-2, rel=0.0, k_scale=8.6e-3, stated_abs=1e-3, stated_rel=2e-2),
 }
 
 
@@ -75,12 +78,15 @@ def check_scalar(name, got, ref, tol, abs_tol=1e-12):
     return err / max(abs(ref), abs_tol)
 
 
-def check_tensor(name, got, ref, kind, scale, oracle_floor=0.0):
-    """Frobenius-relative error against the stated bar, and the derived elementwise bound.
+def check_tensor(name, got, ref, kind, scale, oracle_floor=0.0, k_extra=0.0):
+    """Frobenius-relative error against the stated bar, and the smaller of the two elementwise bounds.
 
     oracle_floor: absolute per-entry uncertainty of the float64 oracle itself.  It forms P_label - 1 by
     subtraction, so when the softmax saturates (P_label = 1 - 1e-29 at s = 100) its gradient entries are
     rounding noise of size 2^-53 * c * s rather than the true 1e-30; callers pass 1e-13 * c * s.
+    k_extra: added to the factor of the derived bound.  A logit held in fp32 is good to |z| * 2^-24, which moves
+    every softmax term by that relative amount; tests whose logits are far larger than CLIP's (features of norm
+    above 1) pass 2^-22 * max|z|.  Zero for every CLIP-like input.
     """
     t = TOL[kind]
     assert np.isfinite(got).all(), f"{name}: non-finite values"
@@ -88,9 +94,9 @@ def check_tensor(name, got, ref, kind, scale, oracle_floor=0.0):
     nd, nr = np.linalg.norm(got - ref), np.linalg.norm(ref)
     fro = nd / max(nr, 1e-300)
     assert nd <= t["frob"] * nr + oracle_floor * np.sqrt(ref.size), f"{name}: Frobenius rel err {fro:.3e} > {t['frob']}"
-    bound = t["rel"] * np.abs(ref) + t["k_scale"] * scale + oracle_floor + 1e-300
+    derived = t["rel"] * np.abs(ref) + (t["k_scale"] + k_extra) * scale
+    stated = t["stated_abs"] * np.abs(ref).max() + t["stated_rel"] * np.abs(ref)
+    bound = np.minimum(derived, stated) + oracle_floor + 1e-300
     ratio = (diff / bound).max()
     assert ratio <= 1.0, f"{name}: elementwise error reaches {ratio:.2f} x its bound (max diff {diff.max():.3e})"
-    if kind == "bf16":
-        assert (diff <= 1e-3 + 2e-2 * np.abs(ref)).all()      # the stated form, literally
     return fro, ratio
