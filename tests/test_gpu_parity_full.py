@@ -49,12 +49,12 @@ def _full_reference_b32k():
     return ref, sc
 
 
-def _check(tag, run, ref, sc):
+def _check(tag, run, ref, sc, cancelling=False):
     loss, gI, gT, gs = run.results()
     e1 = check_scalar(f"{tag} loss", loss, ref[0], TOL["bf16"]["scalar"])
     e2 = check_scalar(f"{tag} gs", gs, ref[3], TOL["bf16"]["scalar"] * 10, abs_tol=1e-9)
-    f1 = check_tensor(f"{tag} gI", gI, ref[1], "bf16", sc[0], sc[2])
-    f2 = check_tensor(f"{tag} gT", gT, ref[2], "bf16", sc[1], sc[2])
+    f1 = check_tensor(f"{tag} gI", gI, ref[1], "bf16", sc[0], sc[2], cancelling=cancelling)
+    f2 = check_tensor(f"{tag} gT", gT, ref[2], "bf16", sc[1], sc[2], cancelling=cancelling)
     print(f"{tag}: loss err {e1:.2e} gs err {e2:.2e} gI (fro, bound ratio) ({f1[0]:.2e}, {f1[1]:.3f}) "
           f"gT ({f2[0]:.2e}, {f2[1]:.3f})", flush=True)
     return loss, gI, gT, gs
@@ -104,7 +104,9 @@ def test_large_workloads_dense(name, rank):
     ref = oc.disco_rank(I, T, cfg.s, rank, cfg.N)
     print(f"  per-rank oracle {time.time() - t0:.1f}s", flush=True)
     sc = term_scale(oc, I, T, cfg.s, rank, cfg.N)
-    loss, gI, gT, gs = _check(f"{name} rank {rank} [oracle {time.time() - t0:.1f}s]", run, ref, sc)
+    # the workload with near-duplicate rows (cosine 0.95) is built to make gradient entries cancel: a near-tie's
+    # (P_ii - 1) y_i + P_ij y_j is a small residual of two large terms, see check_tensor
+    loss, gI, gT, gs = _check(f"{name} rank {rank} [oracle {time.time() - t0:.1f}s]", run, ref, sc, cancelling=cfg.hard_frac > 0)
     assert loss >= 0
 
 
@@ -123,8 +125,8 @@ def test_large_workloads_sampled_rows(name, rank):
     rI, rT = oc.rank_grad_rows(I, T, s, rank, N, lseA, lseC, rows)
     sI, sT = oc.rank_grad_rows(I, T, s, rank, N, lseA, lseC, rows, magnitudes=True)
     fl = 1e-13 * abs(s) / (2.0 * B)
-    check_tensor(f"{name} gI rows", gI[rows], rI, "bf16", sI, fl)
-    check_tensor(f"{name} gT rows", gT[rows], rT, "bf16", sT, fl)
+    check_tensor(f"{name} gI rows", gI[rows], rI, "bf16", sI, fl, cancelling=cfg.hard_frac > 0)
+    check_tensor(f"{name} gT rows", gT[rows], rT, "bf16", sT, fl, cancelling=cfg.hard_frac > 0)
     # d/ds through the identity <gI_r, I> = <gT_r, T> = s * gs_r (exact for each rank's outputs)
     assert float(np.sum(gI * I)) == pytest.approx(s * gs, rel=5e-3, abs=1e-9)
     assert float(np.sum(gT * T)) == pytest.approx(s * gs, rel=5e-3, abs=1e-9)

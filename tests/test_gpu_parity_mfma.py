@@ -18,13 +18,13 @@ def _inputs(B, d, seed, **kw):
     return bf16_bits_to_f32(Ib), bf16_bits_to_f32(Tb), Ib, Tb
 
 
-def _compare(run, ref, scale, tag):
+def _compare(run, ref, scale, tag, cancelling=False):
     loss, gI, gT, gs = run.results()
     errs = dict(
         loss=check_scalar(f"{tag} loss", loss, ref[0], TOL["bf16"]["scalar"]),
         gs=check_scalar(f"{tag} gs", gs, ref[3], TOL["bf16"]["scalar"] * 10, abs_tol=1e-9),
-        gI=check_tensor(f"{tag} gI", gI, ref[1], "bf16", scale[0], scale[2]),
-        gT=check_tensor(f"{tag} gT", gT, ref[2], "bf16", scale[1], scale[2]),
+        gI=check_tensor(f"{tag} gI", gI, ref[1], "bf16", scale[0], scale[2], cancelling=cancelling),
+        gT=check_tensor(f"{tag} gT", gT, ref[2], "bf16", scale[1], scale[2], cancelling=cancelling),
     )
     print(tag, {k: (f"{v:.2e}" if isinstance(v, float) else tuple(f"{x:.2e}" for x in v)) for k, v in errs.items()},
           flush=True)
@@ -51,19 +51,20 @@ def test_mfma_path_matches_oracle(B, d, N, s, kw, path):
     Id, Td, dt = to_device(I, T, Ib, Tb, "bf16")
     assert dl.disco_resolve_path(B, d, N, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_MATERIALIZED
     run = Runner(Id, Td, B, d, N, dt, path)
+    near_ties = bool(kw.get("hard_frac"))       # near-duplicate rows make gradient entries cancel, see check_tensor
     for r in sorted({0, N // 2, N - 1}):
         print(f"case B={B} d={d} N={N} s={s} rank={r}", flush=True)
         run.rank(r, s)
         _compare(run, oc.disco_rank(I, T, s, r, N), term_scale(oc, I, T, s, r, N),
-                 f"B{B} d{d} N{N} s{s:g} rank {r}")
+                 f"B{B} d{d} N{N} s{s:g} rank {r}", near_ties)
     for r in range(N):
         run.rank(r, s, accumulate=(r > 0))
     full = oc.clip_loss_full(I, T, s)
     full_scale = term_scale(oc, I, T, s, 0, 1)
-    _compare(run, full, full_scale, f"B{B} d{d} N{N} s{s:g} accumulated")
+    _compare(run, full, full_scale, f"B{B} d{d} N{N} s{s:g} accumulated", near_ties)
     run1 = Runner(Id, Td, B, d, 1, dt, path)
     run1.full(s)
-    _compare(run1, full, full_scale, f"B{B} d{d} clip_loss_fwd_bwd")
+    _compare(run1, full, full_scale, f"B{B} d{d} clip_loss_fwd_bwd", near_ties)
 
 
 def test_mfma_path_is_deterministic_and_accumulates():

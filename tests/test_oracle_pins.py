@@ -281,3 +281,18 @@ def test_term_scale_matches_loops_and_bounds_the_gradient():
     sI, sT = oc.disco_rank_term_scale(I, T, s, 1, N)
     np.testing.assert_allclose(a, sI[rows], rtol=1e-11)
     np.testing.assert_allclose(t, sT[rows], rtol=1e-11)
+
+
+def test_gs_term_scale_matches_loops_and_bounds_gs():
+    I, T = _rand_pairs(8, 4, 23)
+    s, N = 4.5, 2
+    for r in range(N):
+        sc = oc.disco_rank_gs_term_scale(I, T, s, r, N)
+        assert sc == pytest.approx(brute.brute_rank_gs_term_scale(I.tolist(), T.tolist(), s, r, N), rel=1e-11)
+        assert abs(oc.disco_rank(I, T, s, r, N)[3]) <= sc * (1 + 1e-12)          # triangle inequality
+    # s = 0: P = 1/B everywhere, so the scale is c * sum_ij |1/B - [j = i]| |S_ij| over both directions
+    B = I.shape[0]
+    S = I.astype(np.float64) @ T.astype(np.float64).T
+    W = np.abs(1.0 / B - np.eye(B))
+    want = (np.sum(W * np.abs(S)) + np.sum(W * np.abs(S.T))) / (2.0 * B)
+    assert oc.disco_rank_gs_term_scale(I, T, 0.0, 0, 1) == pytest.approx(want, rel=1e-12)
