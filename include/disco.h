@@ -127,6 +127,25 @@ DISCO_API int clip_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * disco_loss_fwd_bwd for callers that cannot allocate device memory or keep a workspace of their own: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * status codes as disco_loss_fwd_bwd without the workspace pair: the workspace is a static device array of
+ * DISCO_STATIC_SCRATCH_BYTES inside the library (every GPU the library runs on holds its own copy until the
+ * process ends).  The call allocates and frees nothing; on its first use on a device it looks the array's
+ * address up once (not a stream operation: make one call outside any capture first, as for the MFMA paths).
+ * Returns DISCO_ERR_WORKSPACE, before any launch, when the arguments need more than the array holds
+ * (disco_workspace_bytes(...) > disco_static_scratch_bytes()), DISCO_ERR_HIP when the address lookup fails.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or
+ * threads) race on it and must be serialised by the caller; nothing in it needs to start at zero, each call
+ * overwrites what it reads.
+ */
+#define DISCO_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+DISCO_API size_t disco_static_scratch_bytes(void);
+DISCO_API int disco_loss_fwd_bwd_static(const void* I, const void* T, int64_t B, int64_t d, int32_t rank, int32_t N,
+                                        float s, int dtype, int path, int accumulate,
+                                        float* loss, float* gI, float* gT, float* gs, void* hip_stream);
+
+/*
  * Stage timing for benchmarks (measurement only; the paper reports per-operator times in Table 4).
  * `events` is a caller-owned array of `count` hipEvent_t handles (created with timing enabled), or
  * NULL to switch stage timing off (the default).  The setting is process-wide: it is meant for a

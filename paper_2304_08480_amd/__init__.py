@@ -21,6 +21,8 @@ from .binding import (  # noqa: F401
     disco_logit_scale_bwd,
     disco_logit_scale_fwd,
     disco_loss_fwd_bwd,
+    disco_loss_fwd_bwd_static,
+    disco_static_scratch_bytes,
     disco_normalize_bwd,
     disco_normalize_fwd,
     disco_resolve_path,

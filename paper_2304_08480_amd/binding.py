@@ -46,6 +46,10 @@ def _load():
     lib.disco_workspace_bytes.restype = sz
     lib.disco_loss_fwd_bwd.argtypes = [vp, vp, i64, i64, i32, i32, f32, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
     lib.disco_loss_fwd_bwd.restype = ci
+    lib.disco_loss_fwd_bwd_static.argtypes = [vp, vp, i64, i64, i32, i32, f32, ci, ci, ci, vp, vp, vp, vp, vp]
+    lib.disco_loss_fwd_bwd_static.restype = ci
+    lib.disco_static_scratch_bytes.argtypes = []
+    lib.disco_static_scratch_bytes.restype = sz
     lib.clip_loss_fwd_bwd.argtypes = [vp, vp, i64, i64, f32, ci, ci, vp, vp, vp, vp, vp, sz, vp]
     lib.clip_loss_fwd_bwd.restype = ci
     lib.disco_set_stage_events.argtypes = [ctypes.POINTER(vp), ci]
@@ -101,6 +105,19 @@ def disco_loss_fwd_bwd(I, T, B, d, rank, N, s, dtype, path, accumulate, loss, gI
                                  workspace_bytes, _stream_ptr(stream))
     if check and st != DISCO_OK:
         raise DiscoError(st, "disco_loss_fwd_bwd")
+    return st
+
+
+def disco_static_scratch_bytes() -> int:
+    return _lib.disco_static_scratch_bytes()
+
+
+def disco_loss_fwd_bwd_static(I, T, B, d, rank, N, s, dtype, path, accumulate, loss, gI, gT, gs,
+                              stream=None, check=True) -> int:
+    st = _lib.disco_loss_fwd_bwd_static(_ptr(I), _ptr(T), B, d, rank, N, s, dtype, path, int(accumulate),
+                                        _ptr(loss), _ptr(gI), _ptr(gT), _ptr(gs), _stream_ptr(stream))
+    if check and st != DISCO_OK:
+        raise DiscoError(st, "disco_loss_fwd_bwd_static")
     return st
 
 
