@@ -79,6 +79,12 @@ __device__ __forceinline__ float wave_sum(float v) {
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
+// Exponent reference (base 2) of a row: its positive-pair logit, lifted to the row's Cauchy-Schwarz bound minus the
+// headroom where that is larger.  One explicit fma, so that every kernel that forms it gets the same bits.
+__device__ __forceinline__ float row_reference(float zd2, float xnorm, float ymax, float s2) {
+  return fmaxf(zd2, __fmaf_rn(fabsf(s2) * xnorm, ymax, -REF_HEADROOM));
+}
+
 constexpr int NORM_BLOCKS = 512;     // workgroups per matrix that take row norms = partial maxima per matrix
 static_assert(NORM_BLOCKS == NTHREADS, "the logit kernel folds the partial maxima one per thread");
 
@@ -242,8 +248,8 @@ __device__ __forceinline__ void store_staged_numerators(const BlockPtrs& p, cons
 //   STORE: write the bf16 numerators to E (panel-relative columns, 64 x 64 blocked storage, see e_index).
 // materialized path: STATS and STORE, one panel = all keys.  fused path: a STATS-only pass over all
 // keys (nothing of size b x B is written), then STORE-only passes that recompute one panel at a time.
-// A STATS pass derives the rows' exponent references and records them in ref2 (first key tile); a pass without
-// STATS reads them from there, so that it sees the references a repair has replaced.
+// A STATS pass derives the rows' exponent references (row_reference; k_row_merge records the same values in ref2);
+// a pass without STATS reads them from ref2, so that it sees the references a repair has replaced.
 template <bool STATS, bool STORE>
 __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2,
                                                           int64_t jp0, int64_t W, int sbi, int sbj, int nblk) {
@@ -299,12 +305,7 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
 #pragma unroll
       for (int bn = 0; bn < 2; ++bn) {
         const int64_t i = i0 + wn * 64 + bn * 32 + (lane & 31);
-        if (STATS) {
-          ref2[bn] = fmaxf(p.zd2[i], fabsf(s2) * p.xnorm[i] * ymax - REF_HEADROOM);
-          if (jt == 0 && threadIdx.x < NTHREADS / 2 && lane < 32) p.ref2[i] = ref2[bn];
-        } else {
-          ref2[bn] = p.ref2[i];
-        }
+        ref2[bn] = STATS ? row_reference(p.zd2[i], p.xnorm[i], ymax, s2) : p.ref2[i];
       }
     }
     f32x16 acc[4][2];
@@ -338,10 +339,17 @@ __device__ __forceinline__ void row_outputs(const BlockPtrs& p, int64_t i, float
 
 // Row totals -> beta, P_label - 1, cross-entropy.  A workgroup takes 64 rows; its 16 waves each add a
 // sixteenth of the column parts (lane = row, so the reads are coalesced), combined in fixed order.
-__global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int nparts) {
+__global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int nparts, float s2) {
   __shared__ float red[16][64];
+  __shared__ float ymax_w[8];
   const BlockPtrs& p = bl.z[blockIdx.y];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // max_j |y_j| folded from the partial maxima exactly as k_logit_tiles folds it (max is exact in any order)
+  if (threadIdx.x < NORM_BLOCKS) {
+    float m = p.ymax_parts[threadIdx.x];
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (lane == 0) ymax_w[wave] = m;
+  }
   const int64_t i = (int64_t)blockIdx.x * 64 + lane;
   float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
   if (i < b) {
@@ -360,6 +368,10 @@ __global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int np
   float off = 0.f;
 #pragma unroll
   for (int w = 0; w < 16; w += 4) off += (red[w][lane] + red[w + 1][lane]) + (red[w + 2][lane] + red[w + 3][lane]);
+  float ym = ymax_w[0];
+#pragma unroll
+  for (int w = 1; w < 8; ++w) ym = fmaxf(ym, ymax_w[w]);
+  p.ref2[i] = row_reference(p.zd2[i], p.xnorm[i], sqrtf(ym), s2);          // what the statistics pass used for this row
   const float ed = p.ediag[i];
   const float tot = off + ed;
   row_outputs(p, i, off, ed, tot);
@@ -602,7 +614,7 @@ __global__ __launch_bounds__(1024) void k_scalars(Blocks bl, int64_t b, float c,
   }
 }
 
-constexpr int NROWARRAYS = 8;
+constexpr int NROWARRAYS = 7;
 
 struct Plan {
   int64_t b, B, d;
@@ -610,7 +622,7 @@ struct Plan {
   int npanels;
   int nparts;            // B / 128
   int nMq, nN, splitk, ktps;
-  size_t off_E, off_lpart, off_rows, off_Xs, off_part, off_ymax, off_flags, total;
+  size_t off_E, off_lpart, off_rows, off_Xs, off_part, off_ymax, off_flags, off_ref, total;
   size_t rows_stride;    // bytes of one b-float row array (aligned)
 };
 
@@ -651,11 +663,12 @@ Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused) {
   pl.off_E = o;      o += 2 * align_up((size_t)b * pl.W * 2);
   pl.off_lpart = o;  o += 2 * align_up((size_t)pl.nparts * b * 4);
   pl.rows_stride = align_up((size_t)b * 4);
-  pl.off_rows = o;   o += 2 * NROWARRAYS * pl.rows_stride;   // ediag, zd2, xnorm, beta, gdiag, ce, rowds, ref2
+  pl.off_rows = o;   o += 2 * NROWARRAYS * pl.rows_stride;   // ediag, zd2, xnorm, beta, gdiag, ce, rowds
   pl.off_Xs = o;     o += 2 * align_up((size_t)d * b * 2);
   pl.off_part = o;   o += 2 * align_up((size_t)pl.splitk * b * d * 4);
   pl.off_ymax = o;   o += align_up((size_t)2 * NORM_BLOCKS * 4);         // partial maxima of the row norms
   pl.off_flags = o;  o += 2 * align_up((size_t)(b / BN) * 4);            // repair flags, one per query tile
+  pl.off_ref = o;    o += 2 * pl.rows_stride;                            // exponent references of the rows
   pl.total = o;
   return pl;
 }
@@ -704,7 +717,7 @@ int mfma_run(const Problem& pr, bool fused) {
     p.gdiag = reinterpret_cast<float*>(rows + 4 * pl.rows_stride);
     p.ce = reinterpret_cast<float*>(rows + 5 * pl.rows_stride);
     p.rowds = reinterpret_cast<float*>(rows + 6 * pl.rows_stride);
-    p.ref2 = reinterpret_cast<float*>(rows + 7 * pl.rows_stride);
+    p.ref2 = reinterpret_cast<float*>(ws + pl.off_ref + (size_t)z * pl.rows_stride);
     p.tileflag = reinterpret_cast<int*>(ws + pl.off_flags + z * align_up((size_t)(b / BN) * 4));
     p.ymax_parts = wgmax + (z == 0 ? NORM_BLOCKS : 0);     // block A's keys are T, block C's are I
     p.Xs = reinterpret_cast<uint16_t*>(ws + pl.off_Xs + z * align_up((size_t)d * b * 2));
@@ -750,7 +763,7 @@ int mfma_run(const Problem& pr, bool fused) {
     k_logit_tiles<true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, sbi, sbj, 2);
   }
   stage_mark(st, stage++);
-  k_row_merge<<<dim3((unsigned)((b + 63) / 64), 2), 1024, 0, st>>>(bl, b, pl.nparts);
+  k_row_merge<<<dim3((unsigned)((b + 63) / 64), 2), 1024, 0, st>>>(bl, b, pl.nparts, s2);
   if (fused) k_logit_repair<false><<<dim3((unsigned)(2 * nI)), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2);
   else k_logit_repair<true><<<dim3((unsigned)(2 * nI)), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2);
   k_scale_transpose<<<dim3((unsigned)(b / 64), (unsigned)(d / 64), 2), 256, 0, st>>>(bl, b, d);
