@@ -85,3 +85,26 @@ def brute_rank_gs_term_scale(I, T, s, rank, N):
             for j in range(B):
                 total += c * abs(math.exp(s * cos[j] - mx) / den - (1.0 if j == i else 0.0)) * abs(cos[j])
     return total
+
+
+def brute_ntxent_rank(Z, s, rank, N):
+    """Self-supervised (two-view) contrastive loss of rank `rank`, element by element: rows 0..M-1 and M..2M-1 are
+    the two views, the positive of row i is row (i + M) mod 2M, the self-similarity is left out.  Factor 1/B."""
+    B, d = len(Z), len(Z[0])
+    M, b = B // 2, B // N
+    g = [[0.0] * d for _ in range(B)]
+    loss, gs = 0.0, 0.0
+    for i in range(rank * b, (rank + 1) * b):
+        p = (i + M) % B
+        cos = [_dot(Z[i], Z[k]) for k in range(B)]
+        others = [k for k in range(B) if k != i]
+        mx = max(s * cos[k] for k in others)
+        den = math.fsum(math.exp(s * cos[k] - mx) for k in others)
+        loss += (mx + math.log(den) - s * cos[p]) / B
+        for k in others:
+            w = math.exp(s * cos[k] - mx) / den - (1.0 if k == p else 0.0)
+            gs += w * cos[k] / B
+            for c in range(d):
+                g[i][c] += s * w * Z[k][c] / B
+                g[k][c] += s * w * Z[i][c] / B
+    return loss, g, gs
