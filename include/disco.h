@@ -127,6 +127,26 @@ DISCO_API int clip_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The self-supervised contrastive loss on the same decomposition (Sec. 4.1, last sentence, and the Conclusion say
+ * that it applies; the paper prints no formula, so the loss is SimCLR's).  Z (B x d, B = 2M even) holds two views of
+ * M samples, view one in rows 0..M-1 and view two in rows M..2M-1; the positive of row i is row (i + M) mod B and a
+ * row is never its own negative:
+ *     l_i = log sum_{k != i} exp(s <z_i, z_k>) - s <z_i, z_p(i)>,      L = (1/B) sum_i l_i.
+ * Rank r of N owns rows [r*b, (r+1)*b), b = B/N, forms its b x B block of logits and returns, each carrying 1/B so
+ * that the SUM over ranks is the full result: loss_r, gs_r = d loss_r / d s, and gZ_r (B x d fp32): the query-side
+ * gradient in the rank's own rows plus the key-side gradient in all B rows (the part Eq. 5 / Eq. 7 would send to
+ * the other ranks).  Arguments, ownership, errors, paths, `accumulate`, stream and capture rules are those of
+ * disco_loss_fwd_bwd, with one matrix Z for I and T and one gradient gZ; B odd is DISCO_ERR_SHAPE; the bf16 MFMA
+ * paths additionally need (B/2) % 256 == 0.  ntxent_workspace_bytes / ntxent_resolve_path are this entry's
+ * counterparts of disco_workspace_bytes / disco_resolve_path.
+ */
+DISCO_API int ntxent_resolve_path(int64_t B, int64_t d, int32_t N, int dtype, int path);
+DISCO_API size_t ntxent_workspace_bytes(int64_t B, int64_t d, int32_t N, int dtype, int path);
+DISCO_API int ntxent_loss_fwd_bwd(const void* Z, int64_t B, int64_t d, int32_t rank, int32_t N, float s, int dtype, int path,
+                                  int accumulate, float* loss, float* gZ, float* gs,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * disco_loss_fwd_bwd for callers that cannot allocate device memory or keep a workspace of their own: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
  * status codes as disco_loss_fwd_bwd without the workspace pair: the workspace is a static device array of

@@ -30,4 +30,7 @@ from .binding import (  # noqa: F401
     disco_status_string,
     disco_workspace_bytes,
     library_path,
+    ntxent_loss_fwd_bwd,
+    ntxent_resolve_path,
+    ntxent_workspace_bytes,
 )

@@ -52,6 +52,12 @@ def _load():
     lib.disco_static_scratch_bytes.restype = sz
     lib.clip_loss_fwd_bwd.argtypes = [vp, vp, i64, i64, f32, ci, ci, vp, vp, vp, vp, vp, sz, vp]
     lib.clip_loss_fwd_bwd.restype = ci
+    lib.ntxent_resolve_path.argtypes = [i64, i64, i32, ci, ci]
+    lib.ntxent_resolve_path.restype = ci
+    lib.ntxent_workspace_bytes.argtypes = [i64, i64, i32, ci, ci]
+    lib.ntxent_workspace_bytes.restype = sz
+    lib.ntxent_loss_fwd_bwd.argtypes = [vp, i64, i64, i32, i32, f32, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+    lib.ntxent_loss_fwd_bwd.restype = ci
     lib.disco_set_stage_events.argtypes = [ctypes.POINTER(vp), ci]
     lib.disco_set_stage_events.restype = ci
     lib.disco_normalize_fwd.argtypes = [vp, i64, i64, ci, vp, ci, vp, vp]
@@ -127,6 +133,23 @@ def clip_loss_fwd_bwd(I, T, B, d, s, dtype, path, loss, gI, gT, gs, workspace, w
                                 _ptr(gs), _ptr(workspace), workspace_bytes, _stream_ptr(stream))
     if check and st != DISCO_OK:
         raise DiscoError(st, "clip_loss_fwd_bwd")
+    return st
+
+
+def ntxent_resolve_path(B, d, N, dtype, path) -> int:
+    return _lib.ntxent_resolve_path(B, d, N, dtype, path)
+
+
+def ntxent_workspace_bytes(B, d, N, dtype, path) -> int:
+    return _lib.ntxent_workspace_bytes(B, d, N, dtype, path)
+
+
+def ntxent_loss_fwd_bwd(Z, B, d, rank, N, s, dtype, path, accumulate, loss, gZ, gs, workspace, workspace_bytes,
+                        stream=None, check=True) -> int:
+    st = _lib.ntxent_loss_fwd_bwd(_ptr(Z), B, d, rank, N, s, dtype, path, int(accumulate), _ptr(loss), _ptr(gZ),
+                                  _ptr(gs), _ptr(workspace), workspace_bytes, _stream_ptr(stream))
+    if check and st != DISCO_OK:
+        raise DiscoError(st, "ntxent_loss_fwd_bwd")
     return st
 
 

@@ -40,22 +40,31 @@ int check_shape(int64_t B, int64_t d, int32_t N) {
 // 16-byte alignment of the feature matrices: the bf16 tile kernels fetch them in 16-byte pieces
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int resolve(int64_t B, int64_t d, int32_t N, int dtype, int path) {
+int resolve(int64_t B, int64_t d, int32_t N, int dtype, int path, int variant = LOSS_CLIP) {
   int st = check_shape(B, d, N);
   if (st != DISCO_OK) return -st;
+  if (variant == LOSS_NTXENT && B % 2 != 0) return -DISCO_ERR_SHAPE;       // two views of B/2 samples
   if (dtype != DISCO_F32 && dtype != DISCO_BF16) return -DISCO_ERR_UNSUPPORTED;
   switch (path) {
     case DISCO_PATH_AUTO:
-      return mfma_supported(B, d, N, dtype) ? DISCO_PATH_MATERIALIZED : DISCO_PATH_NAIVE;
+      return mfma_supported(B, d, N, dtype, variant) ? DISCO_PATH_MATERIALIZED : DISCO_PATH_NAIVE;
     case DISCO_PATH_NAIVE:
       return DISCO_PATH_NAIVE;
     case DISCO_PATH_MATERIALIZED:
-      return mfma_supported(B, d, N, dtype) ? DISCO_PATH_MATERIALIZED : -DISCO_ERR_UNSUPPORTED;
+      return mfma_supported(B, d, N, dtype, variant) ? DISCO_PATH_MATERIALIZED : -DISCO_ERR_UNSUPPORTED;
     case DISCO_PATH_FUSED:
-      return mfma_supported(B, d, N, dtype) ? DISCO_PATH_FUSED : -DISCO_ERR_UNSUPPORTED;
+      return mfma_supported(B, d, N, dtype, variant) ? DISCO_PATH_FUSED : -DISCO_ERR_UNSUPPORTED;
     default:
       return -DISCO_ERR_UNSUPPORTED;
   }
+}
+
+size_t workspace_need(int r, int64_t B, int64_t d, int32_t N, int variant) {
+  if (r == DISCO_PATH_NAIVE) return naive_workspace_bytes(B, d, N, variant);
+  // (the bf16 paths lay their workspace out for two blocks; the one-block loss uses the first half of each part)
+  if (r == DISCO_PATH_MATERIALIZED) return mfma_stored_workspace_bytes(B, d, N, variant);
+  if (r == DISCO_PATH_FUSED) return mfma_fused_workspace_bytes(B, d, N, variant);
+  return 0;
 }
 
 }  // namespace
@@ -87,6 +96,7 @@ extern "C" int disco_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64
   if (r != DISCO_PATH_NAIVE && !(aligned16(I) && aligned16(T) && aligned16(gI) && aligned16(gT))) return DISCO_ERR_UNSUPPORTED;
 
   Problem p;
+  p.variant = LOSS_CLIP;
   p.I = I; p.T = T; p.B = B; p.d = d; p.rank = rank; p.N = N; p.b = B / N; p.s = s; p.dtype = dtype;
   p.accumulate = accumulate ? 1 : 0;
   p.loss = loss; p.gI = gI; p.gT = gT; p.gs = gs;
@@ -101,6 +111,38 @@ extern "C" int clip_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_
                                  size_t workspace_bytes, void* hip_stream) {
   return disco_loss_fwd_bwd(I, T, B, d, 0, 1, s, dtype, path, 0, loss, gI, gT, gs, workspace, workspace_bytes,
                             hip_stream);
+}
+
+// ---- the self-supervised (two-view) contrastive loss on the same kernels -------------------------------------
+extern "C" int ntxent_resolve_path(int64_t B, int64_t d, int32_t N, int dtype, int path) {
+  return resolve(B, d, N, dtype, path, LOSS_NTXENT);
+}
+
+extern "C" size_t ntxent_workspace_bytes(int64_t B, int64_t d, int32_t N, int dtype, int path) {
+  const int r = resolve(B, d, N, dtype, path, LOSS_NTXENT);
+  return r > 0 ? workspace_need(r, B, d, N, LOSS_NTXENT) : 0;
+}
+
+extern "C" int ntxent_loss_fwd_bwd(const void* Z, int64_t B, int64_t d, int32_t rank, int32_t N, float s, int dtype,
+                                   int path, int accumulate, float* loss, float* gZ, float* gs, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
+  if (!Z || !loss || !gZ || !gs) return DISCO_ERR_NULL;
+  const int r = resolve(B, d, N, dtype, path, LOSS_NTXENT);
+  if (r < 0) return -r;
+  if (rank < 0 || rank >= N) return DISCO_ERR_SHAPE;
+  const size_t need = workspace_need(r, B, d, N, LOSS_NTXENT);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < need)
+    return DISCO_ERR_WORKSPACE;
+  if (r != DISCO_PATH_NAIVE && !(aligned16(Z) && aligned16(gZ))) return DISCO_ERR_UNSUPPORTED;
+  Problem p;
+  p.variant = LOSS_NTXENT;
+  p.I = Z; p.T = Z; p.B = B; p.d = d; p.rank = rank; p.N = N; p.b = B / N; p.s = s; p.dtype = dtype;
+  p.accumulate = accumulate ? 1 : 0;
+  p.loss = loss; p.gI = gZ; p.gT = gZ; p.gs = gs;
+  p.ws = workspace; p.ws_bytes = workspace_bytes;
+  p.stream = static_cast<hipStream_t>(hip_stream);
+  if (r == DISCO_PATH_NAIVE) return naive_run(p);
+  return r == DISCO_PATH_MATERIALIZED ? mfma_stored_run(p) : mfma_fused_run(p);
 }
 
 extern "C" const char* disco_status_string(int status) {

@@ -26,20 +26,34 @@ struct Problem {
   void* ws;
   size_t ws_bytes;
   hipStream_t stream;
+  int variant;        // LOSS_CLIP: two blocks, label = own row.  LOSS_NTXENT: I = T = Z (one matrix, one block,
+                      // gI = gT = gZ), label = the other view's row, the self-similarity is left out
 };
+
+enum { LOSS_CLIP = 0, LOSS_NTXENT = 1 };
+
+// Global row of the positive of global row g, and the column that is left out of row g's softmax (-1: none).
+__host__ __device__ inline int64_t label_row(int64_t g, int64_t B, int variant) {
+  if (variant == LOSS_NTXENT) return g + B / 2 < B ? g + B / 2 : g - B / 2;
+  return g;
+}
+__host__ __device__ inline int64_t masked_col(int64_t g, int variant) { return variant == LOSS_NTXENT ? g : -1; }
+__host__ __device__ inline int loss_blocks(int variant) { return variant == LOSS_NTXENT ? 1 : 2; }
+// Normalisation: 1/(2B) for the two directions of the CLIP loss, 1/B for the single one of the two-view loss.
+__host__ __device__ inline float loss_norm(int64_t B, int variant) { return (variant == LOSS_NTXENT ? 1.0f : 0.5f) / (float)B; }
 
 // Benchmark stage timing (see disco_set_stage_events): records events[k] on `st` if it exists.
 void stage_mark(hipStream_t st, int k);
 
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
-size_t naive_workspace_bytes(int64_t B, int64_t d, int32_t N);
+size_t naive_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant = LOSS_CLIP);
 int naive_run(const Problem& p);
 
-bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype);
-size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N);
+bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype, int variant = LOSS_CLIP);
+size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant = LOSS_CLIP);
 int mfma_stored_run(const Problem& p);
-size_t mfma_fused_workspace_bytes(int64_t B, int64_t d, int32_t N);
+size_t mfma_fused_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant = LOSS_CLIP);
 int mfma_fused_run(const Problem& p);
 
 }  // namespace disco

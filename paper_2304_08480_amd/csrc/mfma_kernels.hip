@@ -69,7 +69,10 @@ struct BlockPtrs {
   float* gq;             // query-side gradient destination (gI for block A, gT for block C), B x d
   float* gk;             // key-side gradient destination, B x d
 };
-struct Blocks { BlockPtrs z[2]; };
+struct Blocks {
+  BlockPtrs z[2];
+  int variant;           // LOSS_CLIP: both blocks.  LOSS_NTXENT: block 0 only (X = Y = Z), see common.h
+};
 
 __device__ __forceinline__ float wave_sum(float v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
@@ -94,7 +97,8 @@ static_assert(NORM_BLOCKS == NTHREADS, "the logit kernel folds the partial maxim
 //    load per lane and row in flight, d is a multiple of 8) and reduces the 8 row sums with interleaved
 //    butterflies.  No atomics: the consumers fold the partial maxima (max is exact, so order does not matter).
 //  * the rest: positive-pair logit and query norm of every local row, one wave per (block, row); the first of
-//    these workgroups also clears the query-tile repair flags of both blocks.
+//    these workgroups also clears the query-tile repair flags of both blocks.  The positive of local row i is
+//    key row label_row(rank b + i): the same global row for the CLIP loss, the other view's row for the two-view loss.
 __global__ __launch_bounds__(256) void k_prep(Blocks bl, const uint16_t* I, const uint16_t* T, int64_t B, int64_t b, int64_t d, int rank,
                                               float s2, float* wgmax) {
   __shared__ float red[4];
@@ -142,7 +146,7 @@ __global__ __launch_bounds__(256) void k_prep(Blocks bl, const uint16_t* I, cons
   const int64_t i = (q % rb) * 4 + wave;
   if (i >= b) return;
   const uint16_t* x = p.X + i * d;
-  const uint16_t* y = p.Y + ((int64_t)rank * b + i) * d;
+  const uint16_t* y = p.Y + label_row((int64_t)rank * b + i, B, bl.variant) * d;
   float dot = 0.f, nn = 0.f;
   for (int64_t k = lane; k < d; k += 64) {
     float xv = __uint_as_float((uint32_t)x[k] << 16), yv = __uint_as_float((uint32_t)y[k] << 16);
@@ -165,12 +169,15 @@ __device__ __forceinline__ int64_t e_index(int64_t i, int64_t jl, int64_t W) {
 // which as direct global stores would be 16-byte fragments; staged as a row-major 256 x 256 bf16 tile (8-byte
 // granules XOR-swizzled with the row: conflict-free 8-byte writes and 16-byte reads) they go out as whole
 // 512-byte row segments.  DIAG: the tile contains label columns, which are stored as 0 and kept in fp32 in ediag.
-// LOCAL (with STATS): the row sums and the label numerators are added into rs / kept in ed (registers of the
-// lane, indexed like ref2) instead of being written to lpart / ediag.
+// The label of query row i is key row lab0 + i; key row self0 + i is left out of row i's softmax (stored as 0, in
+// no sum; self0 far negative: no such column).  LOCAL (with STATS): the row sums and the label numerators are added
+// into rs / kept in ed (registers of the lane, indexed like ref2) instead of being written to lpart / ediag.
+constexpr int64_t NO_SELF = -((int64_t)1 << 40);
+
 template <bool STATS, bool STORE, bool DIAG, bool LOCAL = false>
 __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)[4][2], char* smem, int64_t b, float s2, int64_t i0,
-                                               int64_t j0, int64_t lab0, const float (&ref2)[2], float* rs = nullptr,
-                                               float* ed = nullptr) {
+                                               int64_t j0, int64_t lab0, int64_t self0, const float (&ref2)[2],
+                                               float* rs = nullptr, float* ed = nullptr) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3, half = lane >> 5;
 #pragma unroll
@@ -182,6 +189,8 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
     // [0, 128) means the label is not among this lane's columns)
     const int64_t dl64 = lab0 + i - (j0 + wm * 128 + half * 4);
     const int dl = dl64 >= 0 && dl64 < 128 ? (int)dl64 : -1;
+    const int64_t dm64 = self0 + i - (j0 + wm * 128 + half * 4);
+    const int dm = dm64 >= 0 && dm64 < 128 ? (int)dm64 : -1;
     float rowsum = 0.f;
     char* lrow = smem + il * E_ROW_BYTES;
 #pragma unroll
@@ -200,6 +209,9 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
               else if (STATS) p.ediag[i] = e[r];
               e[r] = 0.f;
             }
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (dm == bm * 32 + q * 8 + r) e[r] = 0.f;
         }
         if (STATS) rowsum += (e[0] + e[1]) + (e[2] + e[3]);
         if (STORE) {
@@ -317,10 +329,13 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
 
-    const int64_t lab0 = (int64_t)rank * b;      // label of query row i is key row lab0 + i
-    // Only the tiles that the label diagonal crosses pay for finding the label column.
-    if ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) logit_epilogue<STATS, STORE, true>(p, acc, smem, b, s2, i0, j0, lab0, ref2);
-    else logit_epilogue<STATS, STORE, false>(p, acc, smem, b, s2, i0, j0, lab0, ref2);
+    // label of query row i is key row lab0 + i (one offset for the whole tile: tiles do not straddle the two views)
+    const int64_t lab0 = label_row((int64_t)rank * b + i0, B, bl.variant) - i0;
+    const int64_t self0 = bl.variant == LOSS_NTXENT ? (int64_t)rank * b : NO_SELF;
+    // Only the tiles that the label diagonal (or the left-out diagonal) crosses pay for finding those columns.
+    const bool diag = ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) || ((self0 + i0 < j0 + BM) && (j0 < self0 + i0 + BN));
+    if (diag) logit_epilogue<STATS, STORE, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, ref2);
+    else logit_epilogue<STATS, STORE, false>(p, acc, smem, b, s2, i0, j0, lab0, self0, ref2);
     if (STORE) store_staged_numerators(p, smem, i0, j0 - jp0, W);
   }
 }
@@ -393,7 +408,9 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
   const BlockPtrs& p = bl.z[z];
   if (p.tileflag[it] == 0) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3, half = lane >> 5;
-  const int64_t i0 = (int64_t)it * BN, lab0 = (int64_t)rank * b;
+  const int64_t i0 = (int64_t)it * BN;
+  const int64_t lab0 = label_row((int64_t)rank * b + i0, B, bl.variant) - i0;
+  const int64_t self0 = bl.variant == LOSS_NTXENT ? (int64_t)rank * b : NO_SELF;
   float* red = reinterpret_cast<float*>(smem);            // [2][256] exchange between the two key halves
   f32x16 acc[4][2];
   float ref2[2] = {-INFINITY, -INFINITY};
@@ -405,12 +422,19 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     mainloop<FMT_K, FMT_K, true>(p.Y + (int64_t)jt * BM * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
+    const int64_t j0 = (int64_t)jt * BM;
+    const bool has_self = (self0 + i0 < j0 + BM) && (j0 < self0 + i0 + BN);   // the left-out column takes no part in the maximum
 #pragma unroll
-    for (int bn = 0; bn < 2; ++bn)
+    for (int bn = 0; bn < 2; ++bn) {
+      const int64_t dm64 = self0 + i0 + wn * 64 + bn * 32 + (lane & 31) - (j0 + wm * 128 + half * 4);
 #pragma unroll
       for (int bm = 0; bm < 4; ++bm)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) ref2[bn] = fmaxf(ref2[bn], acc[bm][bn][e] * s2);
+        for (int e = 0; e < 16; ++e) {
+          const bool skip = has_self && dm64 == bm * 32 + (e >> 2) * 8 + (e & 3);
+          ref2[bn] = skip ? ref2[bn] : fmaxf(ref2[bn], acc[bm][bn][e] * s2);
+        }
+    }
   }
 #pragma unroll
   for (int bn = 0; bn < 2; ++bn) {
@@ -436,8 +460,9 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
-    if ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) logit_epilogue<true, STORE, true, true>(p, acc, smem, b, s2, i0, j0, lab0, ref2, rs, ed);
-    else logit_epilogue<true, STORE, false, true>(p, acc, smem, b, s2, i0, j0, lab0, ref2, rs, ed);
+    const bool diag = ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) || ((self0 + i0 < j0 + BM) && (j0 < self0 + i0 + BN));
+    if (diag) logit_epilogue<true, STORE, true, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, ref2, rs, ed);
+    else logit_epilogue<true, STORE, false, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, ref2, rs, ed);
     if (STORE) store_staged_numerators(p, smem, i0, j0, B);
   }
   // row totals: the four lanes (two key halves x two lane halves) that share a row; exactly one of them met the label
@@ -515,7 +540,7 @@ template <bool ACCUMULATE>
 __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b, int64_t d, int64_t jp0, int64_t W, int nM,
                                                             int nN, int splitk, int ktiles_per_split) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int T = nM * nN, S = 2 * splitk;
+  const int T = nM * nN, S = loss_blocks(bl.variant) * splitk;
   const int w = blockIdx.x, xcd = w & 7, r = w >> 3;
   int slice, tile;
   if (S % 8 == 0) {
@@ -596,11 +621,54 @@ __global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int64_t b, in
   if (lane == 0) { pa.rowds[i] = dot_a; pc.rowds[i] = dot_c; }
 }
 
-// loss_r = c sum ce, gs_r = c sum rowds over both blocks; one workgroup, fixed order.
+// The same for the two-view loss (one block, X = Y = Z, gq = gk = gZ).  With g = rank b + i the row's own global row
+// and lab its positive's row:
+//   gZ[g]   += cs (beta_i sum_ks part + gdiag_i Z[lab])     query side
+//   gZ[lab] += cs gdiag_i Z[g]                              label-column term of the key side
+// The second line lands in another row, lab.  If lab belongs to this rank too, the wave that owns it adds the term
+// (seen from there it reads gdiag_i' Z[lab'] with i' its positive, since the positive of the positive is the row
+// itself); otherwise the wave of row i writes it.  Every row of gZ so has exactly one writer in this kernel.
+__global__ __launch_bounds__(256) void k_query_finalize_ntxent(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float cs, int splitk) {
+  typedef __attribute__((ext_vector_type(4))) float f32x4;
+  const BlockPtrs& p = bl.z[0];
+  const int lane = threadIdx.x & 63;
+  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= b) return;
+  const int64_t g = (int64_t)rank * b + i, lab = label_row(g, B, LOSS_NTXENT);
+  const int64_t ip = lab - (int64_t)rank * b;                         // local index of the positive, if it is local
+  const bool pos_local = ip >= 0 && ip < b;
+  const float beta = p.beta[i], gd = p.gdiag[i], gd_pos = pos_local ? p.gdiag[ip] : 0.f;
+  const uint16_t* Zfull = p.Y;
+  float dot = 0.f;
+  for (int64_t k = lane * 4; k < d; k += 256) {
+    f32x4 u = {0.f, 0.f, 0.f, 0.f};
+    for (int ks = 0; ks < splitk; ++ks) u += *reinterpret_cast<const f32x4*>(p.part + ((int64_t)ks * b + i) * d + k);
+    const u32x2 zw = *reinterpret_cast<const u32x2*>(Zfull + g * d + k);        // Z[g]
+    const u32x2 pw = *reinterpret_cast<const u32x2*>(Zfull + lab * d + k);      // Z[lab]
+    const float zv[4] = {bf16_lo(zw[0]), bf16_hi(zw[0]), bf16_lo(zw[1]), bf16_hi(zw[1])};
+    const float pv[4] = {bf16_lo(pw[0]), bf16_hi(pw[0]), bf16_lo(pw[1]), bf16_hi(pw[1])};
+    f32x4 own = *reinterpret_cast<f32x4*>(p.gq + g * d + k);
+    f32x4 oth = {0.f, 0.f, 0.f, 0.f};
+    if (!pos_local) oth = *reinterpret_cast<f32x4*>(p.gq + lab * d + k);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float ga = fmaf(beta, u[e], gd * pv[e]);
+      own[e] = fmaf(cs * gd_pos, pv[e], fmaf(cs, ga, own[e]));        // + what the local positive owes this row
+      oth[e] = fmaf(cs * gd, zv[e], oth[e]);
+      dot = fmaf(ga, zv[e], dot);
+    }
+    *reinterpret_cast<f32x4*>(p.gq + g * d + k) = own;
+    if (!pos_local) *reinterpret_cast<f32x4*>(p.gq + lab * d + k) = oth;
+  }
+  dot = wave_sum(dot);
+  if (lane == 0) p.rowds[i] = dot;
+}
+
+// loss_r = c sum ce, gs_r = c sum rowds over the blocks of the loss; one workgroup, fixed order.
 __global__ __launch_bounds__(1024) void k_scalars(Blocks bl, int64_t b, float c, int accumulate, float* loss, float* gs) {
   __shared__ float ra[16], rg[16];
   float a = 0.f, g = 0.f;
-  for (int z = 0; z < 2; ++z)
+  for (int z = 0; z < loss_blocks(bl.variant); ++z)
     for (int64_t i = threadIdx.x; i < b; i += 1024) { a += bl.z[z].ce[i]; g += bl.z[z].rowds[i]; }
   a = wave_sum(a);
   g = wave_sum(g);
@@ -634,7 +702,7 @@ int fused_panels(int64_t B) {
   return 1;
 }
 
-Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused) {
+Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused, int nblk = 2) {
   Plan pl;
   pl.B = B; pl.d = d; pl.b = B / N;
   const int64_t b = pl.b;
@@ -653,7 +721,7 @@ Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused) {
   for (int c = 1; c <= 32 && c <= kt_total; ++c) {
     const int ktps = (kt_total + c - 1) / c;
     const int eff = (kt_total + ktps - 1) / ktps;                    // splits that are not empty
-    const int rounds = (2 * tiles * eff + 255) / 256;
+    const int rounds = (nblk * tiles * eff + 255) / 256;
     const double cost = rounds * ktps * 1.1 + eff * (2.0 * b * d * 4.0 * 2.0) / 4e6;
     if (cost < best) { best = cost; sk = c; }
   }
@@ -693,7 +761,8 @@ int mfma_run(const Problem& pr, bool fused) {
                              allow_lds(k_key_grad<true>, GEMM_SMEM_BYTES) && allow_lds(k_query_partial<false>, GEMM_SMEM_BYTES) &&
                              allow_lds(k_query_partial<true>, GEMM_SMEM_BYTES);
   if (!lds_ok) return DISCO_ERR_HIP;
-  const Plan pl = make_plan(pr.B, pr.d, pr.N, fused);
+  const int nblk = loss_blocks(pr.variant);
+  const Plan pl = make_plan(pr.B, pr.d, pr.N, fused, nblk);
   const int persistent_wgs = compute_units();
   const int64_t b = pl.b, B = pl.B, d = pl.d, W = pl.W;
   char* ws = static_cast<char*>(pr.ws);
@@ -702,6 +771,7 @@ int mfma_run(const Problem& pr, bool fused) {
   float* wgmax = reinterpret_cast<float*>(ws + pl.off_ymax);   // NORM_BLOCKS partial maxima of |I_j|^2, then of |T_j|^2
 
   Blocks bl;
+  bl.variant = pr.variant;
   for (int z = 0; z < 2; ++z) {
     BlockPtrs& p = bl.z[z];
     const uint16_t* Xfull = z == 0 ? I : T;
@@ -727,7 +797,7 @@ int mfma_run(const Problem& pr, bool fused) {
   }
 
   const float s2 = pr.s * LOG2E;
-  const float c = 1.0f / (2.0f * (float)B);
+  const float c = loss_norm(B, pr.variant);
   const float cs = c * pr.s;
   hipStream_t st = pr.stream;
   const int nI = (int)(b / BN);
@@ -739,41 +809,41 @@ int mfma_run(const Problem& pr, bool fused) {
     const int nJ = (int)(keys / BM);
     sbj = 32 / sbi;
     while (nJ % sbj) sbj >>= 1;
-    const int tiles2 = 2 * ((nI * nJ + 7) / 8 * 8);     // both blocks, each padded to a multiple of 8
+    const int tiles2 = nblk * ((nI * nJ + 7) / 8 * 8);  // every block, each padded to a multiple of 8
     return dim3((unsigned)(tiles2 < persistent_wgs ? tiles2 : persistent_wgs));
   };
   const int nMk = (int)(W / BM);
-  const dim3 key_grid((unsigned)(((nMk * pl.nN + 7) / 8) * 8), 2);
+  const dim3 key_grid((unsigned)(((nMk * pl.nN + 7) / 8) * 8), (unsigned)nblk);
   // k_query_partial's grid: see its slice -> XCD mapping
-  const int qT = pl.nMq * pl.nN, qS = 2 * pl.splitk;
+  const int qT = pl.nMq * pl.nN, qS = nblk * pl.splitk;
   const int q_wgs = qS % 8 == 0 ? 8 * qT * (qS / 8) : 8 % qS == 0 ? 8 * ((qT + 8 / qS - 1) / (8 / qS)) : (qS * qT + 7) / 8 * 8;
   const dim3 q_grid((unsigned)q_wgs);
   int stage = 0;
 
   stage_mark(st, stage++);
-  k_prep<<<dim3((unsigned)(2 * NORM_BLOCKS + 2 * ((b + 3) / 4))), 256, 0, st>>>(bl, I, T, B, b, d, pr.rank, s2, wgmax);
+  k_prep<<<dim3((unsigned)(2 * NORM_BLOCKS + nblk * ((b + 3) / 4))), 256, 0, st>>>(bl, I, T, B, b, d, pr.rank, s2, wgmax);
   stage_mark(st, stage++);
 
   int sbj;
   if (fused) {
     const dim3 g = logit_grid(B, sbj);
-    k_logit_tiles<true, false><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, sbi, sbj, 2);
+    k_logit_tiles<true, false><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, sbi, sbj, nblk);
   } else {
     const dim3 g = logit_grid(B, sbj);
-    k_logit_tiles<true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, sbi, sbj, 2);
+    k_logit_tiles<true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, sbi, sbj, nblk);
   }
   stage_mark(st, stage++);
-  k_row_merge<<<dim3((unsigned)((b + 63) / 64), 2), 1024, 0, st>>>(bl, b, pl.nparts, s2);
-  if (fused) k_logit_repair<false><<<dim3((unsigned)(2 * nI)), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2);
-  else k_logit_repair<true><<<dim3((unsigned)(2 * nI)), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2);
-  k_scale_transpose<<<dim3((unsigned)(b / 64), (unsigned)(d / 64), 2), 256, 0, st>>>(bl, b, d);
+  k_row_merge<<<dim3((unsigned)((b + 63) / 64), (unsigned)nblk), 1024, 0, st>>>(bl, b, pl.nparts, s2);
+  if (fused) k_logit_repair<false><<<dim3((unsigned)(nblk * nI)), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2);
+  else k_logit_repair<true><<<dim3((unsigned)(nblk * nI)), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2);
+  k_scale_transpose<<<dim3((unsigned)(b / 64), (unsigned)(d / 64), (unsigned)nblk), 256, 0, st>>>(bl, b, d);
   stage_mark(st, stage++);
 
   for (int pnl = 0; pnl < pl.npanels; ++pnl) {
     const int64_t jp0 = (int64_t)pnl * W;
     if (fused) {
       const dim3 g = logit_grid(W, sbj);
-      k_logit_tiles<false, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, jp0, W, sbi, sbj, 2);
+      k_logit_tiles<false, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, jp0, W, sbi, sbj, nblk);
     }
     if (pr.accumulate)
       k_key_grad<true><<<key_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, cs, jp0, W, nMk, pl.nN);
@@ -786,7 +856,8 @@ int mfma_run(const Problem& pr, bool fused) {
       k_query_partial<false><<<q_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, jp0, W, pl.nMq, pl.nN, pl.splitk, pl.ktps);
   }
   stage_mark(st, stage++);
-  k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, b, d, pr.rank, cs, pl.splitk);
+  if (pr.variant == LOSS_NTXENT) k_query_finalize_ntxent<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, b, B, d, pr.rank, cs, pl.splitk);
+  else k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, b, d, pr.rank, cs, pl.splitk);
   k_scalars<<<1, 1024, 0, st>>>(bl, b, c, pr.accumulate, pr.loss, pr.gs);
   stage_mark(st, stage++);
   return hipGetLastError() == hipSuccess ? DISCO_OK : DISCO_ERR_HIP;
@@ -794,18 +865,20 @@ int mfma_run(const Problem& pr, bool fused) {
 
 }  // namespace
 
-bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype) {
+bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype, int variant) {
   if (dtype != DISCO_BF16) return false;
   if (N <= 0 || B % N != 0) return false;
   const int64_t b = B / N;
+  // two-view loss: a 256-row query tile must lie within one view, so that its labels are one offset away
+  if (variant == LOSS_NTXENT && (B % 2 != 0 || (B / 2) % 256 != 0)) return false;
   // per-lane load offsets are 32-bit byte offsets inside one operand tile: 256 rows of pitch b (Xs) or four block
   // rows of pitch 64 W (blocked numerators) must stay below 4 GiB
   if (B > ((int64_t)1 << 23) || b > ((int64_t)1 << 22)) return false;
   return b % 256 == 0 && d % 64 == 0;
 }
 
-size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N) { return make_plan(B, d, N, false).total; }
-size_t mfma_fused_workspace_bytes(int64_t B, int64_t d, int32_t N) { return make_plan(B, d, N, true).total; }
+size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant) { return make_plan(B, d, N, false, loss_blocks(variant)).total; }
+size_t mfma_fused_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant) { return make_plan(B, d, N, true, loss_blocks(variant)).total; }
 int mfma_stored_run(const Problem& pr) { return mfma_run(pr, false); }
 int mfma_fused_run(const Problem& pr) { return mfma_run(pr, true); }
 

@@ -109,19 +109,23 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* red) 
 // W[i][j] <- P_ij - [j = label].  The off-label mass is summed on its own so that P_label - 1 is
 // formed as -(sum of the other terms)/(total) without cancellation.  Also the row's share of
 // d/ds:  sum_j (P_ij - [j=label]) * W_ij.
+// variant LOSS_NTXENT: the positive is the other view's row and column `self` (the row itself) takes no part:
+// it is left out of the maximum and the sums and its gradient entry is 0.
 __global__ __launch_bounds__(256) void naive_row_softmax(float* ws, int64_t b, int64_t B, int rank, float s,
-                                                          float* row_ce, float* row_ds) {
+                                                          float* row_ce, float* row_ds, int variant) {
   __shared__ float red[4];
   const int z = blockIdx.y;
   const int64_t i = blockIdx.x;
   float* w = ws + ((size_t)z * b + i) * B;
-  const int64_t label = (int64_t)rank * b + i;
+  const int64_t label = label_row((int64_t)rank * b + i, B, variant);
+  const int64_t self = masked_col((int64_t)rank * b + i, variant);
   float mx = -INFINITY;
-  for (int64_t j = threadIdx.x; j < B; j += 256) mx = fmaxf(mx, s * w[j]);
+  for (int64_t j = threadIdx.x; j < B; j += 256)
+    if (j != self) mx = fmaxf(mx, s * w[j]);
   mx = block_reduce(mx, true, red);
   float off = 0.f;
   for (int64_t j = threadIdx.x; j < B; j += 256)
-    if (j != label) off += expf(s * w[j] - mx);
+    if (j != label && j != self) off += expf(s * w[j] - mx);
   off = block_reduce(off, false, red);
   const float zl = s * w[label];
   const float el = expf(zl - mx);
@@ -130,7 +134,7 @@ __global__ __launch_bounds__(256) void naive_row_softmax(float* ws, int64_t b, i
   float ds = 0.f;
   for (int64_t j = threadIdx.x; j < B; j += 256) {
     float cs = w[j];
-    float g = (j == label) ? -off * inv : expf(s * cs - mx) * inv;
+    float g = (j == label) ? -off * inv : (j == self) ? 0.f : expf(s * cs - mx) * inv;
     ds = fmaf(g, cs, ds);
     w[j] = g;
   }
@@ -199,32 +203,34 @@ inline unsigned cdiv(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b);
 
 }  // namespace
 
-size_t naive_workspace_bytes(int64_t B, int64_t d, int32_t N) {
+size_t naive_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant) {
   (void)d;
   int64_t b = B / N;
-  return align_up((size_t)2 * b * B * sizeof(float)) + 2 * align_up((size_t)2 * b * sizeof(float));
+  const size_t nb = (size_t)loss_blocks(variant);
+  return align_up(nb * b * B * sizeof(float)) + 2 * align_up(nb * b * sizeof(float));
 }
 
 int naive_run(const Problem& p) {
   const int64_t b = p.b, B = p.B, d = p.d;
   float* W = static_cast<float*>(p.ws);
   char* base = static_cast<char*>(p.ws);
-  float* row_ce = reinterpret_cast<float*>(base + align_up((size_t)2 * b * B * sizeof(float)));
-  float* row_ds = reinterpret_cast<float*>(reinterpret_cast<char*>(row_ce) + align_up((size_t)2 * b * sizeof(float)));
-  const float c = 1.0f / (2.0f * (float)B);
+  const unsigned nb = (unsigned)loss_blocks(p.variant);
+  float* row_ce = reinterpret_cast<float*>(base + align_up((size_t)nb * b * B * sizeof(float)));
+  float* row_ds = reinterpret_cast<float*>(reinterpret_cast<char*>(row_ce) + align_up((size_t)nb * b * sizeof(float)));
+  const float c = loss_norm(B, p.variant);
   const float cs = c * p.s;
 
   stage_mark(p.stream, 0);
-  naive_similarity<<<dim3(cdiv(B, TS), cdiv(b, TS), 2), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W);
+  naive_similarity<<<dim3(cdiv(B, TS), cdiv(b, TS), nb), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W);
   stage_mark(p.stream, 1);
-  naive_row_softmax<<<dim3((unsigned)b, 2), 256, 0, p.stream>>>(W, b, B, p.rank, p.s, row_ce, row_ds);
+  naive_row_softmax<<<dim3((unsigned)b, nb), 256, 0, p.stream>>>(W, b, B, p.rank, p.s, row_ce, row_ds, p.variant);
   stage_mark(p.stream, 2);
-  naive_scalars<<<1, 256, 0, p.stream>>>(row_ce, row_ds, 2 * b, c, p.accumulate, p.loss, p.gs);
+  naive_scalars<<<1, 256, 0, p.stream>>>(row_ce, row_ds, (int64_t)nb * b, c, p.accumulate, p.loss, p.gs);
   stage_mark(p.stream, 3);
-  naive_key_grad<<<dim3(cdiv(B, TS), cdiv(d, TS), 2), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,
+  naive_key_grad<<<dim3(cdiv(B, TS), cdiv(d, TS), nb), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,
                                                                           p.accumulate, p.gI, p.gT);
   stage_mark(p.stream, 4);
-  naive_query_grad<<<dim3(cdiv(d, TS), cdiv(b, TS), 2), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,
+  naive_query_grad<<<dim3(cdiv(d, TS), cdiv(b, TS), nb), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,
                                                                             p.gI, p.gT);
   stage_mark(p.stream, 5);
   return hipGetLastError() == hipSuccess ? DISCO_OK : DISCO_ERR_HIP;

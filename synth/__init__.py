@@ -12,4 +12,5 @@ from .features import (  # noqa: F401
     clip_pairs,
     f32_to_bf16_bits,
     make_config_inputs,
+    two_views,
 )

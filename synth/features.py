@@ -92,6 +92,14 @@ def clip_pairs(B: int, d: int, seed: int, *, noise: float = 0.5,
     return I, T
 
 
+def two_views(M: int, d: int, seed: int, *, noise: float = 0.5) -> np.ndarray:
+    """Features of two views of M samples for a self-supervised contrastive loss, as float32 (2M x d): view one
+    (rows 0..M-1) and view two (rows M..2M-1) of sample i are the two members of clip_pairs' i-th pair, i.e.
+    unit-norm rows with cosine about 0.894 between the views of a sample and near-orthogonal samples."""
+    a, b = clip_pairs(M, d, seed, noise=noise)
+    return np.ascontiguousarray(np.concatenate([a, b], axis=0), dtype=np.float32)
+
+
 ADVERSARIAL_KINDS = ("norms", "permuted", "anti", "duplicates", "zero_rows", "big_norm_low_cos")
 
 

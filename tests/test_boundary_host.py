@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "disco.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b((?:disco|clip)_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b((?:disco|clip|ntxent)_[a-z_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported():
@@ -92,6 +92,28 @@ def test_fused_path_workspace_is_one_key_panel():
     # the two paths may also split the query-side reduction differently (at most 32 partial tiles per block)
     assert mat >= 2 * b * B * 2 and abs((mat - fus) - 2 * b * (B - 16384) * 2) <= 32 * 2 * b * d * 4 and fus < mat
     assert dl.disco_resolve_path(B, d, N, dl.DISCO_F32, dl.DISCO_PATH_FUSED) == -dl.DISCO_ERR_UNSUPPORTED
+
+
+def test_two_view_loss_argument_checks():
+    def call(**kw):
+        a = dict(Z=FAKE, B=256, d=64, rank=0, N=4, s=10.0, dtype=dl.DISCO_F32, path=dl.DISCO_PATH_NAIVE, loss=FAKE, gZ=FAKE,
+                 gs=FAKE, ws=FAKE, ws_bytes=0)
+        a.update(kw)
+        return dl.ntxent_loss_fwd_bwd(a["Z"], a["B"], a["d"], a["rank"], a["N"], a["s"], a["dtype"], a["path"], 0, a["loss"],
+                                      a["gZ"], a["gs"], a["ws"], a["ws_bytes"], None, check=False)
+
+    for name in ("Z", "loss", "gZ", "gs"):
+        assert call(**{name: None}) == dl.DISCO_ERR_NULL
+    assert call(B=255, N=1) == dl.DISCO_ERR_SHAPE                      # two views: an even number of rows
+    assert call(B=256, N=3) == dl.DISCO_ERR_SHAPE and call(rank=4) == dl.DISCO_ERR_SHAPE
+    assert call() == dl.DISCO_ERR_WORKSPACE                            # valid arguments, workspace too small
+    need = dl.ntxent_workspace_bytes(256, 64, 4, dl.DISCO_F32, dl.DISCO_PATH_NAIVE)
+    assert need >= 64 * 256 * 4 and need < 2 * 64 * 256 * 4 + 8192     # ONE b x B block (the CLIP loss keeps two)
+    # the bf16 tile paths need whole 256-row tiles inside one view
+    assert dl.ntxent_resolve_path(1024, 64, 2, dl.DISCO_BF16, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_MATERIALIZED
+    assert dl.ntxent_resolve_path(768, 64, 1, dl.DISCO_BF16, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
+    assert dl.ntxent_resolve_path(768, 64, 1, dl.DISCO_BF16, dl.DISCO_PATH_FUSED) == -dl.DISCO_ERR_UNSUPPORTED
+    assert dl.ntxent_workspace_bytes(255, 64, 1, dl.DISCO_F32, dl.DISCO_PATH_NAIVE) == 0
 
 
 def test_stage_events_argument_check():
