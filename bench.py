@@ -27,6 +27,7 @@ PEAK_FP32_TFLOPS = 157.3      # MI355X fp32 vector
 # loss computation 1.6 ms + loss back-propagation 2.8 ms per iteration and GPU at 512 pairs per GPU of a
 # 32,768 batch (64 A100, mixed precision) = 512 / 4.4 ms pairs per second per rank share.
 PAPER_SAMPLES_PER_S = {"b32k_n64": 512 / 4.4e-3}
+PATH_NAMES = {1: "naive", 2: "materialized", 3: "fused", 4: "symmetric"}
 
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs whose
 # summary is profiles/b32k_n8_hbm_traffic.txt (counters cannot be read from inside this process).
@@ -39,7 +40,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="b32k_n8")
-    ap.add_argument("--path", default="auto", choices=["auto", "naive", "materialized", "fused"])
+    ap.add_argument("--path", default="auto", choices=["auto", "naive", "materialized", "fused", "symmetric"])
     ap.add_argument("--ranks", default="all", help="'all' (every simulated rank per step) or one rank index")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="capture one step (all rank calls) in a graph and time its replays")
@@ -106,7 +107,7 @@ def main():
     cfg = CONFIGS[args.config]
     B, d, N, b, s = cfg.B, cfg.d, cfg.N, cfg.b, cfg.s
     path = {"auto": dl.DISCO_PATH_AUTO, "naive": dl.DISCO_PATH_NAIVE, "materialized": dl.DISCO_PATH_MATERIALIZED,
-            "fused": dl.DISCO_PATH_FUSED}[args.path]
+            "fused": dl.DISCO_PATH_FUSED, "symmetric": dl.DISCO_PATH_SYMMETRIC}[args.path]
     I, T, Ib, Tb = make_config_inputs(cfg)
     dev = torch.device("cuda:0")
     if cfg.dtype == "bf16":
@@ -130,7 +131,7 @@ def main():
         for n, r in enumerate(ranks):
             dl.disco_loss_fwd_bwd(Id, Td, B, d, r, N, s, dt, path, 1 if n > 0 else 0, loss, gI, gT, gs, ws, ws_bytes, stream)
 
-    nstages = 6 if resolved == dl.DISCO_PATH_MATERIALIZED else 5
+    nstages = {dl.DISCO_PATH_MATERIALIZED: 6, dl.DISCO_PATH_SYMMETRIC: 7}.get(resolved, 5)
     ev = HipEvents(nstages + 1)
 
     for _ in range(args.warmup):
@@ -181,13 +182,24 @@ def main():
     ms_per_rank = ms_per_step / calls_per_step
     pairs_per_step = b * calls_per_step
     value = pairs_per_step / (ms_per_step * 1e-3)
-    alg_flops_rank = 12.0 * b * B * d
+    # algorithmic flops of one call: 12 b B d for a rank's two blocks; the non-decomposed loss (N = 1) needs one
+    # similarity matrix for both directions, 6 B^2 d.  Executed: what the path that ran multiplies.
+    alg_flops_rank = 6.0 * B * B * d if N == 1 else 12.0 * b * B * d
+    exec_flops_rank = {dl.DISCO_PATH_SYMMETRIC: 6.0, dl.DISCO_PATH_FUSED: 16.0}.get(resolved, 12.0) * b * B * d
     tflops_alg = alg_flops_rank / (ms_per_rank * 1e-3) / 1e12
+    tflops_exec = exec_flops_rank / (ms_per_rank * 1e-3) / 1e12
 
     if resolved == dl.DISCO_PATH_MATERIALIZED:
         names = ["prep", "logit_tiles", "merge_transpose", "key_grad_gemm", "query_split_gemm", "finalize_scalars"]
         dom = 1
         dom_flops = 4.0 * b * B * d                 # both blocks: 2 * (2 b B d)
+        peak, bound, unit = PEAK_BF16_TFLOPS, "mfma", "TFLOP/s"
+        dtype = "bf16"
+    elif resolved == dl.DISCO_PATH_SYMMETRIC:
+        names = ["prep", "logit_tiles_row_and_column_sums", "merge_transpose", "combine", "key_grad_gemm", "query_split_gemm",
+                 "finalize_scalars"]
+        dom = 1
+        dom_flops = 2.0 * B * B * d                 # one similarity matrix
         peak, bound, unit = PEAK_BF16_TFLOPS, "mfma", "TFLOP/s"
         dtype = "bf16"
     elif resolved == dl.DISCO_PATH_FUSED:
@@ -207,7 +219,7 @@ def main():
     roofline = {
         "bound": bound, "kernel": names[dom], "achieved": round(achieved, 2), "peak": peak, "unit": unit,
         "frac": round(achieved / peak, 4),
-        "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, {1: "naive", 2: "materialized", 3: "fused"}[resolved], names[dom])),
+        "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, PATH_NAMES[resolved], names[dom])),
         "avg_launch_ms": round(dom_ms, 4), "flops_per_launch": dom_flops,
         "stages_ms": {n: round(float(v), 4) for n, v in zip(names, stage_avg)},
     }
@@ -238,12 +250,12 @@ def main():
         "vs_baseline": (round(value / PAPER_SAMPLES_PER_S[cfg.name], 2) if cfg.name in PAPER_SAMPLES_PER_S else None),
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "B": B, "d": d, "N_simulated_ranks": N, "b": b, "s": round(s, 6),
-                   "ranks_per_step": calls_per_step, "path": {1: "naive", 2: "materialized", 3: "fused"}[resolved],
+                   "ranks_per_step": calls_per_step, "path": PATH_NAMES[resolved],
                    "launch": "graph replay" if args.graph else "eager",
                    "workspace_bytes": ws_bytes},
         "ms_per_step_median": round(step_ms[len(step_ms) // 2], 4), "ms_per_step_min": round(step_ms[0], 4),
         "ms_per_rank_call": round(ms_per_rank, 4),
-        "tflops_algorithmic": round(tflops_alg, 2),
+        "tflops_algorithmic": round(tflops_alg, 2), "tflops_executed": round(tflops_exec, 2),
         "frac_of_bf16_mfma_peak_algorithmic": round(tflops_alg / PEAK_BF16_TFLOPS, 4),
         "wall_ms_per_step": round((wall1 - wall0) * 1e3 / args.steps, 4),
         "loss": float(loss.item()),

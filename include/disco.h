@@ -77,8 +77,16 @@ typedef enum { DISCO_F32 = 0, DISCO_BF16 = 1 } disco_dtype;
  *                         key panel (at most 16384 keys) at a time and contracts each panel while
  *                         it is cache-resident (16*b*B*d flop, workspace 2*b*W*2 bytes for panel
  *                         width W).  Same shape limits as MATERIALIZED.
- * DISCO_PATH_AUTO         the fastest path that supports the arguments: MATERIALIZED when its shape
- *                         limits hold, else NAIVE.  Shares that are not a multiple of 256 pairs, feature
+ * DISCO_PATH_SYMMETRIC    bf16 MFMA tiles, N = 1 only (the non-decomposed loss, Eq. 1 / Fig. 1): the B x B
+ *                         similarity matrix is computed once and serves both directions (text -> image is
+ *                         its transpose); one matrix of numerators (B*B*2 bytes) against one exponent
+ *                         reference, turned in place into the combined gradient matrix, then one contraction
+ *                         per feature gradient: 6*B^2*d flop instead of 12.  Same shape limits as
+ *                         MATERIALIZED.  Inputs whose rows' or columns' largest logits lie more than about
+ *                         60 (base 2) under the largest positive-pair logit are handed over, inside the same
+ *                         call, to the MATERIALIZED kernels, so the workspace is sized for those as well.
+ * DISCO_PATH_AUTO         the fastest path that supports the arguments: SYMMETRIC (N = 1) or MATERIALIZED
+ *                         when their shape limits hold, else NAIVE.  Shares that are not a multiple of 256 pairs, feature
  *                         widths that are not a multiple of 64 and fp32 inputs therefore run on the vector
  *                         ALUs, an order of magnitude slower; disco_resolve_path tells which path a call takes.
  */
@@ -86,7 +94,8 @@ typedef enum {
   DISCO_PATH_AUTO = 0,
   DISCO_PATH_NAIVE = 1,
   DISCO_PATH_MATERIALIZED = 2,
-  DISCO_PATH_FUSED = 3
+  DISCO_PATH_FUSED = 3,
+  DISCO_PATH_SYMMETRIC = 4
 } disco_path;
 
 /* The concrete path (1..3) that `path` resolves to for these arguments, or a negative
@@ -119,8 +128,9 @@ DISCO_API int disco_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_
 
 /*
  * The original non-distributed CLIP loss (Eq. 1, Fig. 1): the whole B x B similarity matrix on
- * one device.  Equal in value to disco_loss_fwd_bwd(rank = 0, N = 1, accumulate = 0); the
- * workspace size is disco_workspace_bytes(B, d, 1, dtype, path).
+ * one device.  Equal in value to disco_loss_fwd_bwd(rank = 0, N = 1, accumulate = 0) and the same call
+ * (DISCO_PATH_AUTO resolves to DISCO_PATH_SYMMETRIC when the shape allows); the workspace size is
+ * disco_workspace_bytes(B, d, 1, dtype, path).
  */
 DISCO_API int clip_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t d, float s, int dtype, int path,
                       float* loss, float* gI, float* gT, float* gs,
@@ -180,11 +190,15 @@ DISCO_API int disco_loss_fwd_bwd_static(const void* I, const void* T, int64_t B,
  * Stages of DISCO_PATH_FUSED (DISCO_STAGES_FUSED = 5): row norms + positive-pair logits, streaming forward
  *   (row sums only), row merge + scaled transpose, all key panels (recompute + both gradient GEMMs),
  *   query finalize + scalars.
+ * Stages of DISCO_PATH_SYMMETRIC (DISCO_STAGES_SYMMETRIC = 7): row norms + positive-pair logits + reference, logit
+ *   tiles with row and column sums, both merges + transpose, combining pass, key-side GEMM, query-side split GEMM,
+ *   finalize + scalars.
  * Returns DISCO_OK, or DISCO_ERR_SHAPE if count < 0.
  */
 #define DISCO_STAGES_MATERIALIZED 6
 #define DISCO_STAGES_NAIVE 5
 #define DISCO_STAGES_FUSED 5
+#define DISCO_STAGES_SYMMETRIC 7
 DISCO_API int disco_set_stage_events(void** events, int count);
 
 /*

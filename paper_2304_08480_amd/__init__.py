@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     DISCO_PATH_FUSED,
     DISCO_PATH_MATERIALIZED,
     DISCO_PATH_NAIVE,
+    DISCO_PATH_SYMMETRIC,
     DiscoError,
     clip_loss_fwd_bwd,
     disco_logit_scale_bwd,

@@ -16,7 +16,7 @@ import torch  # noqa: F401  (import order matters)
 DISCO_OK = 0
 DISCO_ERR_NULL, DISCO_ERR_SHAPE, DISCO_ERR_UNSUPPORTED, DISCO_ERR_WORKSPACE, DISCO_ERR_HIP = 1, 2, 3, 4, 5
 DISCO_F32, DISCO_BF16 = 0, 1
-DISCO_PATH_AUTO, DISCO_PATH_NAIVE, DISCO_PATH_MATERIALIZED, DISCO_PATH_FUSED = 0, 1, 2, 3
+DISCO_PATH_AUTO, DISCO_PATH_NAIVE, DISCO_PATH_MATERIALIZED, DISCO_PATH_FUSED, DISCO_PATH_SYMMETRIC = 0, 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdisco.so")

@@ -47,13 +47,16 @@ int resolve(int64_t B, int64_t d, int32_t N, int dtype, int path, int variant = 
   if (dtype != DISCO_F32 && dtype != DISCO_BF16) return -DISCO_ERR_UNSUPPORTED;
   switch (path) {
     case DISCO_PATH_AUTO:
-      return mfma_supported(B, d, N, dtype, variant) ? DISCO_PATH_MATERIALIZED : DISCO_PATH_NAIVE;
+      if (!mfma_supported(B, d, N, dtype, variant)) return DISCO_PATH_NAIVE;
+      return N == 1 && variant == LOSS_CLIP ? DISCO_PATH_SYMMETRIC : DISCO_PATH_MATERIALIZED;
     case DISCO_PATH_NAIVE:
       return DISCO_PATH_NAIVE;
     case DISCO_PATH_MATERIALIZED:
       return mfma_supported(B, d, N, dtype, variant) ? DISCO_PATH_MATERIALIZED : -DISCO_ERR_UNSUPPORTED;
     case DISCO_PATH_FUSED:
       return mfma_supported(B, d, N, dtype, variant) ? DISCO_PATH_FUSED : -DISCO_ERR_UNSUPPORTED;
+    case DISCO_PATH_SYMMETRIC:
+      return N == 1 && variant == LOSS_CLIP && mfma_supported(B, d, N, dtype, variant) ? DISCO_PATH_SYMMETRIC : -DISCO_ERR_UNSUPPORTED;
     default:
       return -DISCO_ERR_UNSUPPORTED;
   }
@@ -64,6 +67,7 @@ size_t workspace_need(int r, int64_t B, int64_t d, int32_t N, int variant) {
   // (the bf16 paths lay their workspace out for two blocks; the one-block loss uses the first half of each part)
   if (r == DISCO_PATH_MATERIALIZED) return mfma_stored_workspace_bytes(B, d, N, variant);
   if (r == DISCO_PATH_FUSED) return mfma_fused_workspace_bytes(B, d, N, variant);
+  if (r == DISCO_PATH_SYMMETRIC) return mfma_sym_workspace_bytes(B, d);
   return 0;
 }
 
@@ -74,11 +78,8 @@ extern "C" int disco_resolve_path(int64_t B, int64_t d, int32_t N, int dtype, in
 }
 
 extern "C" size_t disco_workspace_bytes(int64_t B, int64_t d, int32_t N, int dtype, int path) {
-  int r = resolve(B, d, N, dtype, path);
-  if (r == DISCO_PATH_NAIVE) return naive_workspace_bytes(B, d, N);
-  if (r == DISCO_PATH_MATERIALIZED) return mfma_stored_workspace_bytes(B, d, N);
-  if (r == DISCO_PATH_FUSED) return mfma_fused_workspace_bytes(B, d, N);
-  return 0;
+  const int r = resolve(B, d, N, dtype, path);
+  return r > 0 ? workspace_need(r, B, d, N, LOSS_CLIP) : 0;
 }
 
 extern "C" int disco_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t d, int32_t rank, int32_t N,
@@ -88,9 +89,7 @@ extern "C" int disco_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64
   int r = resolve(B, d, N, dtype, path);
   if (r < 0) return -r;
   if (rank < 0 || rank >= N) return DISCO_ERR_SHAPE;
-  size_t need = r == DISCO_PATH_NAIVE          ? naive_workspace_bytes(B, d, N)
-                : r == DISCO_PATH_MATERIALIZED ? mfma_stored_workspace_bytes(B, d, N)
-                                               : mfma_fused_workspace_bytes(B, d, N);
+  const size_t need = workspace_need(r, B, d, N, LOSS_CLIP);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < need)
     return DISCO_ERR_WORKSPACE;
   if (r != DISCO_PATH_NAIVE && !(aligned16(I) && aligned16(T) && aligned16(gI) && aligned16(gT))) return DISCO_ERR_UNSUPPORTED;
@@ -103,6 +102,7 @@ extern "C" int disco_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64
   p.ws = workspace; p.ws_bytes = workspace_bytes;
   p.stream = static_cast<hipStream_t>(hip_stream);
   if (r == DISCO_PATH_NAIVE) return naive_run(p);
+  if (r == DISCO_PATH_SYMMETRIC) return mfma_sym_run(p);
   return r == DISCO_PATH_MATERIALIZED ? mfma_stored_run(p) : mfma_fused_run(p);
 }
 

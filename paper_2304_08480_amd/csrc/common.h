@@ -55,5 +55,7 @@ size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant 
 int mfma_stored_run(const Problem& p);
 size_t mfma_fused_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant = LOSS_CLIP);
 int mfma_fused_run(const Problem& p);
+size_t mfma_sym_workspace_bytes(int64_t B, int64_t d);
+int mfma_sym_run(const Problem& p);      // N = 1, the CLIP loss only
 
 }  // namespace disco

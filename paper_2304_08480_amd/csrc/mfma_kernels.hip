@@ -71,8 +71,13 @@ struct BlockPtrs {
 };
 struct Blocks {
   BlockPtrs z[2];
-  int variant;           // LOSS_CLIP: both blocks.  LOSS_NTXENT: block 0 only (X = Y = Z), see common.h
+  int variant;           // LOSS_CLIP or LOSS_NTXENT (label and left-out column of a row, see common.h)
+  int nblk;              // blocks in use: 2 for the CLIP loss, 1 for the two-view loss and for the symmetric full loss
+  const int* gate;       // nullptr: the kernel always runs; else it runs only while *gate == gate_value (the symmetric
+  int gate_value;        // full-loss path hands over to the two-block path through this flag)
 };
+
+__device__ __forceinline__ bool gated_off(const Blocks& bl) { return bl.gate != nullptr && *bl.gate != bl.gate_value; }
 
 __device__ __forceinline__ float wave_sum(float v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
@@ -101,6 +106,7 @@ static_assert(NORM_BLOCKS == NTHREADS, "the logit kernel folds the partial maxim
 //    key row label_row(rank b + i): the same global row for the CLIP loss, the other view's row for the two-view loss.
 __global__ __launch_bounds__(256) void k_prep(Blocks bl, const uint16_t* I, const uint16_t* T, int64_t B, int64_t b, int64_t d, int rank,
                                               float s2, float* wgmax) {
+  if (gated_off(bl)) return;
   __shared__ float red[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (blockIdx.x < 2 * NORM_BLOCKS) {
@@ -265,6 +271,7 @@ __device__ __forceinline__ void store_staged_numerators(const BlockPtrs& p, cons
 template <bool STATS, bool STORE>
 __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2,
                                                           int64_t jp0, int64_t W, int sbi, int sbj, int nblk) {
+  if (gated_off(bl)) return;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   // Persistent workgroups (one per compute unit) walk the tile lists of the nblk blocks in bl, one after the
   // other, with a stride of the grid size: a wave ends only when all its stores are acknowledged, so ending a
@@ -354,7 +361,13 @@ __device__ __forceinline__ void row_outputs(const BlockPtrs& p, int64_t i, float
 
 // Row totals -> beta, P_label - 1, cross-entropy.  A workgroup takes 64 rows; its 16 waves each add a
 // sixteenth of the column parts (lane = row, so the reads are coalesced), combined in fixed order.
-__global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int nparts, float s2) {
+// nparts0 / nparts1: number of partial sums per row of block 0 / block 1.  global_ref (symmetric full loss): the one
+// exponent reference every row shares; bad_flag: where that path records that a row or column total was lost
+// (the per-rank paths flag the row's query tile for repair instead).
+__global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int nparts0, int nparts1, float s2,
+                                                    const float* global_ref, int* bad_flag) {
+  if (gated_off(bl)) return;
+  const int nparts = blockIdx.y ? nparts1 : nparts0;
   __shared__ float red[16][64];
   __shared__ float ymax_w[8];
   const BlockPtrs& p = bl.z[blockIdx.y];
@@ -386,13 +399,16 @@ __global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int np
   float ym = ymax_w[0];
 #pragma unroll
   for (int w = 1; w < 8; ++w) ym = fmaxf(ym, ymax_w[w]);
-  p.ref2[i] = row_reference(p.zd2[i], p.xnorm[i], sqrtf(ym), s2);          // what the statistics pass used for this row
+  p.ref2[i] = global_ref ? *global_ref : row_reference(p.zd2[i], p.xnorm[i], sqrtf(ym), s2);   // what the statistics pass used
   const float ed = p.ediag[i];
   const float tot = off + ed;
   row_outputs(p, i, off, ed, tot);
   // The guard lifted the reference so far above every logit of this row that its total is (next to) lost:
   // the row's query tile is redone against the true row maximum.  Also catches non-finite totals.
-  if (!(tot >= ROW_TOTAL_FLOOR)) p.tileflag[i >> 8] = 1;
+  if (!(tot >= ROW_TOTAL_FLOOR)) {
+    if (bad_flag) *bad_flag = 1;
+    else p.tileflag[i >> 8] = 1;
+  }
 }
 
 // The statistics kernels of a flagged query tile, redone by one workgroup per (block, query tile): a first
@@ -402,6 +418,7 @@ __global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int np
 // at once, which is the normal case: the kernel then costs one launch.
 template <bool STORE>
 __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2) {
+  if (gated_off(bl)) return;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int nI = (int)(b / BN), nJ = (int)(B / BM);
   const int z = blockIdx.x / nI, it = blockIdx.x % nI;
@@ -489,14 +506,16 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
 }
 
 // Xs[k][i] = bf16(beta_i * x_ik): the key-side contraction's right operand with the reduction index contiguous.
-__global__ __launch_bounds__(256) void k_scale_transpose(Blocks bl, int64_t b, int64_t d) {
+// scaled = 0: plain transpose (the symmetric full loss folds both normalisations into the stored matrix instead).
+__global__ __launch_bounds__(256) void k_scale_transpose(Blocks bl, int64_t b, int64_t d, int scaled) {
+  if (gated_off(bl)) return;
   __shared__ float tile[64][65];
   const BlockPtrs& p = bl.z[blockIdx.z];
   const int64_t i0 = (int64_t)blockIdx.x * 64, k0 = (int64_t)blockIdx.y * 64;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   for (int r = ty; r < 64; r += 4) {
     const int64_t i = i0 + r;
-    tile[r][tx] = p.beta[i] * __uint_as_float((uint32_t)p.X[i * d + k0 + tx] << 16);
+    tile[r][tx] = (scaled ? p.beta[i] : 1.f) * __uint_as_float((uint32_t)p.X[i * d + k0 + tx] << 16);
   }
   __syncthreads();
   for (int r = ty; r < 64; r += 4) {
@@ -511,6 +530,7 @@ __global__ __launch_bounds__(256) void k_scale_transpose(Blocks bl, int64_t b, i
 template <bool ACCUMULATE>
 __global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int64_t d, float cs, int64_t jp0, int64_t W,
                                                        int nM, int nN) {
+  if (gated_off(bl)) return;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const BlockPtrs& p = bl.z[blockIdx.y];
   int lin;
@@ -539,8 +559,9 @@ __global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int
 template <bool ACCUMULATE>
 __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b, int64_t d, int64_t jp0, int64_t W, int nM,
                                                             int nN, int splitk, int ktiles_per_split) {
+  if (gated_off(bl)) return;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int T = nM * nN, S = loss_blocks(bl.variant) * splitk;
+  const int T = nM * nN, S = bl.nblk * splitk;
   const int w = blockIdx.x, xcd = w & 7, r = w >> 3;
   int slice, tile;
   if (S % 8 == 0) {
@@ -583,6 +604,7 @@ __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b
 //   gT[lab] += cs (beta^C_i sum_ks part^C + gdiag^C_i I[lab]) + cs gdiag^A_i I[lab]
 // and the rows' shares of d/ds, <query-side vector, x_i>, per block.  One wave per row, fixed summation order.
 __global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int64_t b, int64_t d, int rank, float cs, int splitk) {
+  if (gated_off(bl)) return;
   typedef __attribute__((ext_vector_type(4))) float f32x4;
   const BlockPtrs& pa = bl.z[0];
   const BlockPtrs& pc = bl.z[1];
@@ -629,6 +651,7 @@ __global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int64_t b, in
 // (seen from there it reads gdiag_i' Z[lab'] with i' its positive, since the positive of the positive is the row
 // itself); otherwise the wave of row i writes it.  Every row of gZ so has exactly one writer in this kernel.
 __global__ __launch_bounds__(256) void k_query_finalize_ntxent(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float cs, int splitk) {
+  if (gated_off(bl)) return;
   typedef __attribute__((ext_vector_type(4))) float f32x4;
   const BlockPtrs& p = bl.z[0];
   const int lane = threadIdx.x & 63;
@@ -666,9 +689,10 @@ __global__ __launch_bounds__(256) void k_query_finalize_ntxent(Blocks bl, int64_
 
 // loss_r = c sum ce, gs_r = c sum rowds over the blocks of the loss; one workgroup, fixed order.
 __global__ __launch_bounds__(1024) void k_scalars(Blocks bl, int64_t b, float c, int accumulate, float* loss, float* gs) {
+  if (gated_off(bl)) return;
   __shared__ float ra[16], rg[16];
   float a = 0.f, g = 0.f;
-  for (int z = 0; z < loss_blocks(bl.variant); ++z)
+  for (int z = 0; z < bl.nblk; ++z)
     for (int64_t i = threadIdx.x; i < b; i += 1024) { a += bl.z[z].ce[i]; g += bl.z[z].rowds[i]; }
   a = wave_sum(a);
   g = wave_sum(g);
@@ -680,6 +704,178 @@ __global__ __launch_bounds__(1024) void k_scalars(Blocks bl, int64_t b, float c,
     *loss = (accumulate ? *loss : 0.f) + c * sa;
     *gs = (accumulate ? *gs : 0.f) + c * sg;
   }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Symmetric full loss (N = 1; Eq. 1 / Fig. 1: one B x B similarity matrix serves both directions, text -> image is
+// its transpose).  z2_ij = s2 <I_i, T_j> is computed once and kept as ONE matrix of numerators against ONE reference r,
+//   E_ij = exp2(z2_ij - r),      r = max(max_i z2_ii, s2 max|I_i| max|T_j| - headroom),
+// whose row sums normalise image -> text (beta^A_i) and whose column sums normalise text -> image (beta^C_j).  A
+// second pass turns it in place into the combined gradient matrix G_ij = E_ij (beta^A_i + beta^C_j) = P^A_ij + P^C_ji
+// (bf16, label entries kept apart in fp32 as before), so that each feature gradient is one contraction:
+//   gT = cs G^T I,   gI = cs G T     ->   2 + 4 = 6 B^2 d flop instead of 12.
+// One reference for all rows and columns needs every row's and column's largest logit within about 60 (base 2)
+// of r + 0; where a total falls under the floor, k_row_merge raises the flag at `gate`, the remaining kernels of
+// this path return at once and the two-block path, launched behind them and gated the other way, does the call.
+
+// r of the comment above, and the hand-over flag cleared.  One workgroup.
+__global__ __launch_bounds__(1024) void k_sym_ref(const float* zd2, int64_t B, const float* wgmax, float s2, float* rglobal, int* gate) {
+  __shared__ float red[16], nrm[2][16];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float m = -INFINITY;
+  for (int64_t i = threadIdx.x; i < B; i += 1024) m = fmaxf(m, zd2[i]);
+  float n0 = wgmax[threadIdx.x % NORM_BLOCKS], n1 = wgmax[NORM_BLOCKS + threadIdx.x % NORM_BLOCKS];
+  for (int o = 32; o > 0; o >>= 1) {
+    m = fmaxf(m, __shfl_xor(m, o));
+    n0 = fmaxf(n0, __shfl_xor(n0, o));
+    n1 = fmaxf(n1, __shfl_xor(n1, o));
+  }
+  if (lane == 0) { red[wave] = m; nrm[0][wave] = n0; nrm[1][wave] = n1; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float a = red[0], x = nrm[0][0], y = nrm[1][0];
+    for (int w = 1; w < 16; ++w) { a = fmaxf(a, red[w]); x = fmaxf(x, nrm[0][w]); y = fmaxf(y, nrm[1][w]); }
+    *rglobal = row_reference(a, sqrtf(x), sqrtf(y), s2);
+    *gate = 0;
+  }
+}
+
+// Logit tiles of the symmetric path: k_logit_tiles for one block (X = I on the tile's N side, Y = T on its M side)
+// with the one reference; the row sums come from the accumulators as there, the column sums (over the tile's
+// query rows) from the staged bf16 tile while it is copied out: a thread adds up its 8 columns over its 16 rows,
+// lanes l and l + 32 join, the eight waves leave their sums in ring unit 4 and, after the barrier that ends the
+// copy, 256 threads add the eight.  (So the text -> image normalisation is that of the stored, rounded numerators.)
+// bl.z[0]: E, row partial sums, label numerators; bl.z[1].lpart: column partial sums, one per query tile, cpart[it][j].
+__global__ __launch_bounds__(NTHREADS) void k_sym_logit(Blocks bl, int64_t B, int64_t d, float s2, const float* rglobal, int sbi, int sbj) {
+  if (gated_off(bl)) return;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const BlockPtrs& p = bl.z[0];
+  const int nI = (int)(B / BN), nJ = (int)(B / BM);
+  const int total = nI * nJ;
+  const int chunk = (total + 7) >> 3, padded = chunk << 3;
+  const float ref = *rglobal;
+  const float ref2[2] = {ref, ref};
+  float* colpart = reinterpret_cast<float*>(smem + E_TILE_BYTES);       // [8 waves][256 keys]
+  for (int u = blockIdx.x; u < padded; u += gridDim.x) {
+    const int lin = (u & 7) * chunk + (u >> 3);
+    if ((u >> 3) >= chunk || lin >= total) continue;
+    const int sbsz = sbi * sbj, sb = lin / sbsz, within = lin % sbsz;
+    const int nSBi = nI / sbi;
+    const int it = (sb % nSBi) * sbi + within % sbi;
+    const int jt = (sb / nSBi) * sbj + within / sbi;
+    const int64_t i0 = (int64_t)it * BN, j0 = (int64_t)jt * BM;
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
+    // the label of query row i is key row i: only the tiles on the diagonal contain label columns
+    if (it == jt) logit_epilogue<true, true, true>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, ref2);
+    else logit_epilogue<true, true, false>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, ref2);
+    lds_barrier();
+    const int t = threadIdx.x;
+    const int chunk16 = t & 31, r0 = t >> 5;
+    float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+    for (int r = 0; r < 16; ++r) {
+      const int row = r * 16 + r0;
+      const u32x4 raw = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + ((chunk16 ^ ((row & 31) >> 1)) << 4));
+      const u32x4 val = (row & 1) ? u32x4{raw[2], raw[3], raw[0], raw[1]} : raw;
+      // read again by the combining pass and the two contractions: ordinary stores
+      *reinterpret_cast<u32x4*>(p.E + e_index(i0 + row, j0 + chunk16 * 8, B)) = val;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        cs[2 * w] += bf16_lo(val[w]);
+        cs[2 * w + 1] += bf16_hi(val[w]);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) cs[k] += __shfl_xor(cs[k], 32);
+    if ((t & 63) < 32) {
+      float* cp = colpart + (t >> 6) * 256 + chunk16 * 8;
+      *reinterpret_cast<f32x4*>(cp) = f32x4{cs[0], cs[1], cs[2], cs[3]};
+      *reinterpret_cast<f32x4*>(cp + 4) = f32x4{cs[4], cs[5], cs[6], cs[7]};
+    }
+    lds_barrier();
+    if (t < BM) {
+      float c = 0.f;
+#pragma unroll
+      for (int w = 0; w < 8; ++w) c += colpart[w * 256 + t];
+      bl.z[1].lpart[(int64_t)it * B + j0 + t] = c;
+    }
+  }
+}
+
+// G_ij = E_ij (beta^A_i + beta^C_j) in place, bf16 (nearest even); the label entries stay 0.  A workgroup takes
+// 64 x 64 blocks of the blocked matrix one after the other; a thread 2 x 8 consecutive entries of a block.
+__global__ __launch_bounds__(256) void k_sym_combine(Blocks bl, int64_t B) {
+  if (gated_off(bl)) return;
+  const float* betaA = bl.z[0].beta;
+  const float* betaC = bl.z[1].beta;
+  uint16_t* E = bl.z[0].E;
+  const int64_t nb = B >> 6, nblocks = nb * nb;
+  const int t = threadIdx.x;
+  for (int64_t blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
+    const int64_t ib = blk / nb, jb = blk % nb;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int c = h * 256 + t;                          // 16-byte chunk of the block: row c >> 3, columns 8 (c & 7) ..
+      const int row = c >> 3, col = (c & 7) * 8;
+      u32x4* ptr = reinterpret_cast<u32x4*>(E + blk * 4096 + row * 64 + col);
+      const u32x4 raw = *ptr;
+      const float ba = betaA[ib * 64 + row];
+      const f32x4 bc0 = *reinterpret_cast<const f32x4*>(betaC + jb * 64 + col);
+      const f32x4 bc1 = *reinterpret_cast<const f32x4*>(betaC + jb * 64 + col + 4);
+      const float bc[8] = {bc0[0], bc0[1], bc0[2], bc0[3], bc1[0], bc1[1], bc1[2], bc1[3]};
+      u32x4 out;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const __bf16 lo = (__bf16)(bf16_lo(raw[w]) * (ba + bc[2 * w]));
+        const __bf16 hi = (__bf16)(bf16_hi(raw[w]) * (ba + bc[2 * w + 1]));
+        out[w] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+      }
+      *ptr = out;
+    }
+  }
+}
+
+// Row i of both gradients, for the symmetric path (every row is an own row): with u = sum_ks part[ks][i] = (G T)_i
+// without the label entry and gd = (P^A_ii - 1) + (P^C_ii - 1),
+//   gI[i] (+)= cs (u + gd T[i])      gT[i] += cs gd I[i]   (the key-side contraction has written or added its part)
+// and the row's share of d/ds, <u + gd T[i], I[i]> (sum_ij G_ij S_ij = <G T, I> with the label entries included).
+__global__ __launch_bounds__(256) void k_sym_finalize(Blocks bl, int64_t B, int64_t d, float cs, int splitk, int accumulate) {
+  if (gated_off(bl)) return;
+  const BlockPtrs& p = bl.z[0];
+  const int lane = threadIdx.x & 63;
+  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= B) return;
+  const float gd = p.gdiag[i] + bl.z[1].gdiag[i];
+  float dot = 0.f;
+  for (int64_t k = lane * 4; k < d; k += 256) {
+    f32x4 u = {0.f, 0.f, 0.f, 0.f};
+    for (int ks = 0; ks < splitk; ++ks) u += *reinterpret_cast<const f32x4*>(p.part + ((int64_t)ks * B + i) * d + k);
+    const u32x2 iw = *reinterpret_cast<const u32x2*>(p.X + i * d + k);
+    const u32x2 tw = *reinterpret_cast<const u32x2*>(p.Y + i * d + k);
+    const float iv[4] = {bf16_lo(iw[0]), bf16_hi(iw[0]), bf16_lo(iw[1]), bf16_hi(iw[1])};
+    const float tv[4] = {bf16_lo(tw[0]), bf16_hi(tw[0]), bf16_lo(tw[1]), bf16_hi(tw[1])};
+    f32x4 gi = {0.f, 0.f, 0.f, 0.f};
+    if (accumulate) gi = *reinterpret_cast<const f32x4*>(p.gq + i * d + k);
+    f32x4 gt = *reinterpret_cast<const f32x4*>(p.gk + i * d + k);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float ga = fmaf(gd, tv[e], u[e]);
+      gi[e] = fmaf(cs, ga, gi[e]);
+      gt[e] = fmaf(cs * gd, iv[e], gt[e]);
+      dot = fmaf(ga, iv[e], dot);
+    }
+    *reinterpret_cast<f32x4*>(p.gq + i * d + k) = gi;
+    *reinterpret_cast<f32x4*>(p.gk + i * d + k) = gt;
+  }
+  dot = wave_sum(dot);
+  if (lane == 0) { p.rowds[i] = dot; bl.z[1].rowds[i] = 0.f; }
 }
 
 constexpr int NROWARRAYS = 7;
@@ -753,7 +949,8 @@ bool allow_lds(K kernel, int bytes) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess;
 }
 
-int mfma_run(const Problem& pr, bool fused) {
+// gate / gate_value: see Blocks.  marks: record the benchmark's stage events.
+int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_value = 0, bool marks = true) {
   // the tile kernels use more LDS than the default limit; raised once per process (one device per process here)
   static const bool lds_ok = allow_lds(k_logit_tiles<true, true>, LOGIT_SMEM_BYTES) && allow_lds(k_logit_tiles<true, false>, LOGIT_SMEM_BYTES) &&
                              allow_lds(k_logit_tiles<false, true>, LOGIT_SMEM_BYTES) && allow_lds(k_logit_repair<false>, LOGIT_SMEM_BYTES) &&
@@ -772,6 +969,9 @@ int mfma_run(const Problem& pr, bool fused) {
 
   Blocks bl;
   bl.variant = pr.variant;
+  bl.nblk = nblk;
+  bl.gate = gate;
+  bl.gate_value = gate_value;
   for (int z = 0; z < 2; ++z) {
     BlockPtrs& p = bl.z[z];
     const uint16_t* Xfull = z == 0 ? I : T;
@@ -820,9 +1020,9 @@ int mfma_run(const Problem& pr, bool fused) {
   const dim3 q_grid((unsigned)q_wgs);
   int stage = 0;
 
-  stage_mark(st, stage++);
+  if (marks) stage_mark(st, stage++);
   k_prep<<<dim3((unsigned)(2 * NORM_BLOCKS + nblk * ((b + 3) / 4))), 256, 0, st>>>(bl, I, T, B, b, d, pr.rank, s2, wgmax);
-  stage_mark(st, stage++);
+  if (marks) stage_mark(st, stage++);
 
   int sbj;
   if (fused) {
@@ -832,12 +1032,12 @@ int mfma_run(const Problem& pr, bool fused) {
     const dim3 g = logit_grid(B, sbj);
     k_logit_tiles<true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, sbi, sbj, nblk);
   }
-  stage_mark(st, stage++);
-  k_row_merge<<<dim3((unsigned)((b + 63) / 64), (unsigned)nblk), 1024, 0, st>>>(bl, b, pl.nparts, s2);
+  if (marks) stage_mark(st, stage++);
+  k_row_merge<<<dim3((unsigned)((b + 63) / 64), (unsigned)nblk), 1024, 0, st>>>(bl, b, pl.nparts, pl.nparts, s2, nullptr, nullptr);
   if (fused) k_logit_repair<false><<<dim3((unsigned)(nblk * nI)), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2);
   else k_logit_repair<true><<<dim3((unsigned)(nblk * nI)), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2);
-  k_scale_transpose<<<dim3((unsigned)(b / 64), (unsigned)(d / 64), (unsigned)nblk), 256, 0, st>>>(bl, b, d);
-  stage_mark(st, stage++);
+  k_scale_transpose<<<dim3((unsigned)(b / 64), (unsigned)(d / 64), (unsigned)nblk), 256, 0, st>>>(bl, b, d, 1);
+  if (marks) stage_mark(st, stage++);
 
   for (int pnl = 0; pnl < pl.npanels; ++pnl) {
     const int64_t jp0 = (int64_t)pnl * W;
@@ -849,18 +1049,123 @@ int mfma_run(const Problem& pr, bool fused) {
       k_key_grad<true><<<key_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, cs, jp0, W, nMk, pl.nN);
     else
       k_key_grad<false><<<key_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, cs, jp0, W, nMk, pl.nN);
-    if (!fused) stage_mark(st, stage++);
+    if (!fused) if (marks) stage_mark(st, stage++);
     if (pnl > 0)
       k_query_partial<true><<<q_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, jp0, W, pl.nMq, pl.nN, pl.splitk, pl.ktps);
     else
       k_query_partial<false><<<q_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, jp0, W, pl.nMq, pl.nN, pl.splitk, pl.ktps);
   }
-  stage_mark(st, stage++);
+  if (marks) stage_mark(st, stage++);
   if (pr.variant == LOSS_NTXENT) k_query_finalize_ntxent<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, b, B, d, pr.rank, cs, pl.splitk);
   else k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, b, d, pr.rank, cs, pl.splitk);
   k_scalars<<<1, 1024, 0, st>>>(bl, b, c, pr.accumulate, pr.loss, pr.gs);
-  stage_mark(st, stage++);
+  if (marks) stage_mark(st, stage++);
   return hipGetLastError() == hipSuccess ? DISCO_OK : DISCO_ERR_HIP;
+}
+
+// The symmetric full loss (see the kernels above): one matrix of numerators, both directions' statistics, one
+// combined gradient matrix, two contractions; then, behind the flag, the two-block path for inputs it cannot take.
+size_t sym_tail(int64_t B, int64_t d) {
+  const size_t a = make_plan(B, d, 1, false, 1).total, c = make_plan(B, d, 1, false, 2).total;
+  return a > c ? a : c;
+}
+
+int mfma_sym_run_impl(const Problem& pr) {
+  static const bool lds_ok = allow_lds(k_sym_logit, LOGIT_SMEM_BYTES);
+  if (!lds_ok) return DISCO_ERR_HIP;
+  const Plan pl = make_plan(pr.B, pr.d, 1, false, 1);
+  const int persistent_wgs = compute_units();
+  const int64_t B = pl.B, d = pl.d;
+  char* ws = static_cast<char*>(pr.ws);
+  const size_t tail = sym_tail(B, d);
+  int* gate = reinterpret_cast<int*>(ws + tail);
+  float* rglobal = reinterpret_cast<float*>(ws + tail + 128);
+  const uint16_t* I = static_cast<const uint16_t*>(pr.I);
+  const uint16_t* T = static_cast<const uint16_t*>(pr.T);
+  float* wgmax = reinterpret_cast<float*>(ws + pl.off_ymax);
+
+  Blocks bl;
+  bl.variant = LOSS_CLIP;
+  bl.nblk = 1;
+  bl.gate = nullptr;
+  bl.gate_value = 0;
+  BlockPtrs& p = bl.z[0];
+  char* rows0 = ws + pl.off_rows;
+  char* rows1 = rows0 + (size_t)NROWARRAYS * pl.rows_stride;
+  p.X = I;
+  p.Y = T;
+  p.E = reinterpret_cast<uint16_t*>(ws + pl.off_E);
+  p.lpart = reinterpret_cast<float*>(ws + pl.off_lpart);
+  p.ediag = reinterpret_cast<float*>(rows0 + 0 * pl.rows_stride);
+  p.zd2 = reinterpret_cast<float*>(rows0 + 1 * pl.rows_stride);
+  p.xnorm = reinterpret_cast<float*>(rows0 + 2 * pl.rows_stride);
+  p.beta = reinterpret_cast<float*>(rows0 + 3 * pl.rows_stride);
+  p.gdiag = reinterpret_cast<float*>(rows0 + 4 * pl.rows_stride);
+  p.ce = reinterpret_cast<float*>(rows0 + 5 * pl.rows_stride);
+  p.rowds = reinterpret_cast<float*>(rows0 + 6 * pl.rows_stride);
+  p.ref2 = reinterpret_cast<float*>(ws + pl.off_ref);
+  p.tileflag = reinterpret_cast<int*>(ws + pl.off_flags);
+  p.ymax_parts = wgmax + NORM_BLOCKS;
+  p.Xs = reinterpret_cast<uint16_t*>(ws + pl.off_Xs);
+  p.part = reinterpret_cast<float*>(ws + pl.off_part);
+  p.gq = pr.gI;
+  p.gk = pr.gT;
+  // "block 1" holds the column side: partial column sums and the text -> image statistics; label numerators,
+  // positive-pair logits and the reference are the row side's
+  BlockPtrs& q = bl.z[1];
+  q = p;
+  q.lpart = reinterpret_cast<float*>(ws + pl.off_lpart + align_up((size_t)pl.nparts * B * 4));
+  q.beta = reinterpret_cast<float*>(rows1 + 3 * pl.rows_stride);
+  q.gdiag = reinterpret_cast<float*>(rows1 + 4 * pl.rows_stride);
+  q.ce = reinterpret_cast<float*>(rows1 + 5 * pl.rows_stride);
+  q.rowds = reinterpret_cast<float*>(rows1 + 6 * pl.rows_stride);
+  q.ref2 = reinterpret_cast<float*>(ws + pl.off_ref + pl.rows_stride);
+  q.tileflag = reinterpret_cast<int*>(ws + pl.off_flags + align_up((size_t)(B / BN) * 4));
+
+  const float s2 = pr.s * LOG2E;
+  const float c = loss_norm(B, LOSS_CLIP);
+  const float cs = c * pr.s;
+  hipStream_t st = pr.stream;
+  const int nT = (int)(B / BN);
+  int sbi = 8;
+  while (nT % sbi) sbi >>= 1;
+  int sbj = 32 / sbi;
+  while (nT % sbj) sbj >>= 1;
+  const int tiles = (nT * nT + 7) / 8 * 8;
+  const dim3 logit_grid((unsigned)(tiles < persistent_wgs ? tiles : persistent_wgs));
+  const dim3 key_grid((unsigned)(((nT * pl.nN + 7) / 8) * 8), 1);
+  const int qT = pl.nMq * pl.nN, qS = pl.splitk;
+  const int q_wgs = qS % 8 == 0 ? 8 * qT * (qS / 8) : 8 % qS == 0 ? 8 * ((qT + 8 / qS - 1) / (8 / qS)) : (qS * qT + 7) / 8 * 8;
+  int stage = 0;
+
+  stage_mark(st, stage++);
+  k_prep<<<dim3((unsigned)(2 * NORM_BLOCKS + (B + 3) / 4)), 256, 0, st>>>(bl, I, T, B, B, d, 0, s2, wgmax);
+  k_sym_ref<<<1, 1024, 0, st>>>(p.zd2, B, wgmax, s2, rglobal, gate);
+  stage_mark(st, stage++);
+  k_sym_logit<<<logit_grid, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, B, d, s2, rglobal, sbi, sbj);
+  stage_mark(st, stage++);
+  Blocks both = bl;
+  both.nblk = 2;
+  k_row_merge<<<dim3((unsigned)((B + 63) / 64), 2), 1024, 0, st>>>(both, B, pl.nparts, nT, s2, rglobal, gate);
+  Blocks go = bl;                                   // from here on only while no total was lost
+  go.gate = gate;
+  go.gate_value = 0;
+  k_scale_transpose<<<dim3((unsigned)(B / 64), (unsigned)(d / 64), 1), 256, 0, st>>>(go, B, d, 0);
+  stage_mark(st, stage++);
+  k_sym_combine<<<dim3((unsigned)(8 * persistent_wgs)), 256, 0, st>>>(go, B);
+  stage_mark(st, stage++);
+  if (pr.accumulate) k_key_grad<true><<<key_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(go, B, d, cs, 0, B, nT, pl.nN);
+  else k_key_grad<false><<<key_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(go, B, d, cs, 0, B, nT, pl.nN);
+  stage_mark(st, stage++);
+  k_query_partial<false><<<dim3((unsigned)q_wgs), NTHREADS, GEMM_SMEM_BYTES, st>>>(go, B, d, 0, B, pl.nMq, pl.nN, pl.splitk, pl.ktps);
+  stage_mark(st, stage++);
+  k_sym_finalize<<<dim3((unsigned)((B + 3) / 4)), 256, 0, st>>>(go, B, d, cs, pl.splitk, pr.accumulate);
+  Blocks go2 = go;
+  go2.nblk = 2;
+  k_scalars<<<1, 1024, 0, st>>>(go2, B, c, pr.accumulate, pr.loss, pr.gs);
+  stage_mark(st, stage++);
+  if (hipGetLastError() != hipSuccess) return DISCO_ERR_HIP;
+  return mfma_run(pr, false, gate, 1, false);
 }
 
 }  // namespace
@@ -881,5 +1186,7 @@ size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant)
 size_t mfma_fused_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant) { return make_plan(B, d, N, true, loss_blocks(variant)).total; }
 int mfma_stored_run(const Problem& pr) { return mfma_run(pr, false); }
 int mfma_fused_run(const Problem& pr) { return mfma_run(pr, true); }
+size_t mfma_sym_workspace_bytes(int64_t B, int64_t d) { return sym_tail(B, d) + 256; }
+int mfma_sym_run(const Problem& pr) { return mfma_sym_run_impl(pr); }
 
 }  // namespace disco

@@ -63,6 +63,24 @@ def test_adversarial_inputs_match_oracle(path, kind, s):
              _zmax(I, T, s), oc.disco_rank_gs_term_scale(I, T, s, 0, 1))
 
 
+@pytest.mark.parametrize("s", [14.285714, 100.0], ids=["s14", "s100"])
+@pytest.mark.parametrize("kind", ADVERSARIAL_KINDS)
+def test_adversarial_inputs_symmetric_full_loss(kind, s):
+    """The symmetric path of the non-decomposed loss keeps one matrix of numerators against one reference; inputs
+    whose row or column totals that loses (anti-correlated positives at s = 100, rows far below their bound) must
+    be handed over to the two-block kernels inside the call and still match the oracle."""
+    B, d = 1024, 256
+    I, T = adversarial_pairs(B, d, 13, kind)
+    Ib, Tb = f32_to_bf16_bits(I), f32_to_bf16_bits(T)
+    I, T = bf16_bits_to_f32(Ib), bf16_bits_to_f32(Tb)
+    Id, Td, dt = to_device(I, T, Ib, Tb, "bf16")
+    run = Runner(Id, Td, B, d, 1, dt, dl.DISCO_PATH_SYMMETRIC)
+    print(f"case symmetric {kind} s={s}", flush=True)
+    run.full(s)
+    _compare(run, oc.clip_loss_full(I, T, s), term_scale(oc, I, T, s, 0, 1), "bf16", f"symmetric {kind} s{s:g}", _zmax(I, T, s),
+             oc.disco_rank_gs_term_scale(I, T, s, 0, 1))
+
+
 def test_rows_far_below_their_bound_take_the_slow_path():
     """big_norm_low_cos at s = 1/0.07: the reference derived from the norms lies more than 160 (base 2) above
     every logit of every row, so the first pass loses all row totals and every query tile is redone against the

@@ -34,7 +34,7 @@ def _setup(name, N=None, path=dl.DISCO_PATH_AUTO):
     N = cfg.N if N is None else N
     run = Runner(Id, Td, cfg.B, cfg.d, N, dt, path)
     if path == dl.DISCO_PATH_AUTO:
-        assert dl.disco_resolve_path(cfg.B, cfg.d, N, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_MATERIALIZED
+        assert dl.disco_resolve_path(cfg.B, cfg.d, N, dt, dl.DISCO_PATH_AUTO) == (dl.DISCO_PATH_MATERIALIZED if N > 1 else dl.DISCO_PATH_SYMMETRIC)
     return cfg, I, T, run
 
 
@@ -84,9 +84,11 @@ def test_b32k_n8_accumulated_against_the_full_loss():
     assert np.sum(gT * T) == pytest.approx(cfg.s * gs, rel=2e-3)
 
 
-@pytest.mark.parametrize("path", [dl.DISCO_PATH_MATERIALIZED, dl.DISCO_PATH_FUSED], ids=["materialized", "fused"])
+@pytest.mark.parametrize("path", [dl.DISCO_PATH_AUTO, dl.DISCO_PATH_MATERIALIZED, dl.DISCO_PATH_FUSED],
+                         ids=["auto_symmetric", "materialized", "fused"])
 def test_full_n1_against_the_full_loss(path):
-    """The non-decomposed entry point at B=32768 (the whole 32768 x 32768 matrix on one device), both bf16 paths."""
+    """The non-decomposed entry point at B=32768 (the whole 32768 x 32768 matrix on one device): the symmetric path
+    that AUTO takes and both two-block bf16 paths."""
     cfg, I, T, run = _setup("b32k_n8", N=1, path=path)
     print(f"case full_n1 path {path}", flush=True)
     run.full(cfg.s)
