@@ -44,7 +44,7 @@ def parse():
     ap.add_argument("--ranks", default="all", help="'all' (every simulated rank per step) or one rank index")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="capture one step (all rank calls) in a graph and time its replays")
-    ap.add_argument("--op", default="loss", choices=["loss", "prep"],
+    ap.add_argument("--op", default="loss", choices=["loss", "prep", "mfma-peak"],
                     help="'loss': the hot path (default, the headline line); 'prep': the feature normalisation "
                          "forward + backward on both feature matrices of the workload (HBM-bound, reported in GB/s)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -103,6 +103,8 @@ def main():
 
     if args.op == "prep":
         return bench_prep(args, dl, CONFIGS[args.config], np, torch)
+    if args.op == "mfma-peak":
+        return bench_mfma_peak(args, dl, np, torch)
 
     cfg = CONFIGS[args.config]
     B, d, N, b, s = cfg.B, cfg.d, cfg.N, cfg.b, cfg.s
@@ -262,6 +264,44 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    print(json.dumps(out))
+
+
+def bench_mfma_peak(args, dl, np, torch):
+    """What the matrix cores sustain with every compute unit issuing bf16 MFMAs from registers and nothing else
+    (no memory traffic), after `warmup` launches of about 5 ms each, and the shader clock meanwhile.  This is the
+    ceiling the clock management leaves under the published 2.5 PFLOP/s; the tile kernels work against it."""
+    dev = torch.device("cuda:0")
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    sink = torch.zeros(1, device=dev)
+    clocks = torch.zeros(2, dtype=torch.int64, device=dev)
+    stream = torch.cuda.current_stream()
+    iters = 40000                                   # x 8 MFMAs x 32768 flop per wave
+    rows = []
+    for wgs in (cus // 4, cus):                     # a quarter of the chip busy, then all of it
+        for _ in range(max(args.warmup, 20)):
+            dl.disco_mfma_probe(wgs, iters, sink, clocks, stream)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record(stream)
+        for _ in range(args.steps):
+            dl.disco_mfma_probe(wgs, iters, sink, clocks, stream)
+        b.record(stream)
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / args.steps
+        c = clocks.cpu().numpy()
+        flops = wgs * 8 * iters * 8 * 32768.0
+        rows.append({"workgroups": wgs, "ms_per_launch": round(ms, 4), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+                     "shader_clock_mhz": round(100.0 * float(c[0]) / float(c[1]), 1)})
+    full = rows[-1]
+    out = {"metric": "bf16 MFMA issue rate, registers only, all compute units", "value": full["tflops"], "unit": "TFLOP/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": max(args.warmup, 20), "ms_per_step": full["ms_per_launch"],
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "mfma-peak", "compute_units": cus, "waves_per_simd": 2, "mfma": "v_mfma_f32_32x32x16_bf16"},
+           "runs": rows,
+           "roofline": {"bound": "mfma", "kernel": "k_mfma_probe", "achieved": full["tflops"], "peak": PEAK_BF16_TFLOPS,
+                        "unit": "TFLOP/s", "frac": round(full["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None},
+           "cpu_baseline": None}
     print(json.dumps(out))
 
 

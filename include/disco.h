@@ -202,6 +202,15 @@ DISCO_API int disco_loss_fwd_bwd_static(const void* I, const void* T, int64_t B,
 DISCO_API int disco_set_stage_events(void** events, int count);
 
 /*
+ * Measurement only: `workgroups` workgroups of 8 waves each issue `iters` x 8 bf16 MFMA 32x32x16 instructions per
+ * wave (32768 flop each) from registers, with no memory traffic: what the matrix cores sustain once the clock
+ * management has settled, the ceiling under the published peak that a tile kernel works against.  sink: one device
+ * float (never written); clocks: two device uint64, filled by workgroup 0 with its elapsed shader-clock ticks and
+ * its elapsed ticks of the fixed 100 MHz counter (their ratio is the shader clock in units of 100 MHz).
+ */
+DISCO_API int disco_mfma_probe(int workgroups, int iters, float* sink, unsigned long long* clocks, void* hip_stream);
+
+/*
  * Feature preparation on either side of the loss.  In Alg. 1 the encoders hand the features to the loss
  * and take the feature gradients back; the paper prints neither the row normalisation nor the
  * parametrisation of `t`.  Reading taken (CLIP's convention): unit-norm rows, u = x / max(|x|, 1e-12),

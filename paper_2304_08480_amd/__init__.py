@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     disco_logit_scale_bwd,
     disco_logit_scale_fwd,
     disco_loss_fwd_bwd,
+    disco_mfma_probe,
     disco_loss_fwd_bwd_static,
     disco_static_scratch_bytes,
     disco_normalize_bwd,

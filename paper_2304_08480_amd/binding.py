@@ -68,6 +68,8 @@ def _load():
     lib.disco_logit_scale_fwd.restype = ci
     lib.disco_logit_scale_bwd.argtypes = [vp, f32, vp, vp, ci, vp]
     lib.disco_logit_scale_bwd.restype = ci
+    lib.disco_mfma_probe.argtypes = [ci, ci, vp, vp, vp]
+    lib.disco_mfma_probe.restype = ci
     lib.disco_status_string.argtypes = [ci]
     lib.disco_status_string.restype = ctypes.c_char_p
     return lib
@@ -156,6 +158,13 @@ def ntxent_loss_fwd_bwd(Z, B, d, rank, N, s, dtype, path, accumulate, loss, gZ, 
 def disco_set_stage_events(events, count: int) -> int:
     """`events`: a ctypes array of c_void_p holding hipEvent_t handles (kept alive by the caller), or None."""
     return _lib.disco_set_stage_events(events, int(count))
+
+
+def disco_mfma_probe(workgroups, iters, sink, clocks, stream=None, check=True) -> int:
+    st = _lib.disco_mfma_probe(int(workgroups), int(iters), _ptr(sink), _ptr(clocks), _stream_ptr(stream))
+    if check and st != DISCO_OK:
+        raise DiscoError(st, "disco_mfma_probe")
+    return st
 
 
 def disco_normalize_fwd(X, rows, d, x_dtype, U, u_dtype, inv_norm, stream=None, check=True) -> int:

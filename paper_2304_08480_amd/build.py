@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdisco.so")
-SOURCES = ["api.hip", "naive_kernels.hip", "mfma_kernels.hip", "prep_kernels.hip", "static_entry.hip"]
+SOURCES = ["api.hip", "naive_kernels.hip", "mfma_kernels.hip", "prep_kernels.hip", "static_entry.hip", "probe_kernels.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
