@@ -30,8 +30,10 @@ PAPER_SAMPLES_PER_S = {"b32k_n64": 512 / 4.4e-3}
 PATH_NAMES = {1: "naive", 2: "materialized", 3: "fused", 4: "symmetric"}
 
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs whose
-# summary is profiles/b32k_n8_hbm_traffic.txt (counters cannot be read from inside this process).
-MEASURED_TRAFFIC_BYTES = {("b32k_n8", "materialized", "logit_tiles"): 8.857e8}
+# summary is profiles/b32k_n8_hbm_traffic.txt (counters cannot be read from inside this process; the fetch part
+# varies by about a quarter from run to run with what the last-level cache still holds).  Only the headline
+# workload has such a summary: every other workload and path reports null on purpose.
+MEASURED_TRAFFIC_BYTES = {("b32k_n8", "materialized", "logit_tiles"): 9.796e8}
 
 
 def parse():
@@ -55,13 +57,18 @@ def parse():
 class HipEvents:
     """hipEvent_t handles created through the HIP runtime already loaded by torch."""
 
-    def __init__(self, n):
+    def __init__(self, n, only=None):
+        """n handles; with `only` (a set of indices) the other entries stay NULL and the library skips them."""
+        # (events released to device scope: a default event has the stream write the L2 back for the host at
+        # every record)
         self.hip = ctypes.CDLL("libamdhip64.so.7") if _loaded("libamdhip64.so.7") else ctypes.CDLL("libamdhip64.so")
         self.n = n
         self.arr = (ctypes.c_void_p * n)()
         for i in range(n):
+            if only is not None and i not in only:
+                continue
             ev = ctypes.c_void_p()
-            assert self.hip.hipEventCreate(ctypes.byref(ev)) == 0
+            assert self.hip.hipEventCreateWithFlags(ctypes.byref(ev), ctypes.c_uint(0x40000000)) == 0
             self.arr[i] = ev
 
     def elapsed_ms(self, a, b):
@@ -134,7 +141,6 @@ def main():
             dl.disco_loss_fwd_bwd(Id, Td, B, d, r, N, s, dt, path, 1 if n > 0 else 0, loss, gI, gT, gs, ws, ws_bytes, stream)
 
     nstages = {dl.DISCO_PATH_MATERIALIZED: 6, dl.DISCO_PATH_SYMMETRIC: 7}.get(resolved, 5)
-    ev = HipEvents(nstages + 1)
 
     for _ in range(args.warmup):
         step()
@@ -165,19 +171,30 @@ def main():
     step_ms = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
 
     # stage intervals: the same steps again with the library recording HIP events between its stages on the
-    # stream it launches on; averaged over every rank call of `stage_steps` steps
-    dl.disco_set_stage_events(ev.arr, ev.n)
+    # stream it launches on.  Every rank call gets an event set of its own and nothing synchronises until all calls
+    # of `stage_steps` steps are enqueued, so that the kernels run in the same back-to-back stream (same clocks) as
+    # in the timed region; averaged over every rank call.  An event between two kernels keeps the second from being
+    # set up under the first one's tail: the intervals add up to 5-8 % more than a call takes without them.  They are
+    # therefore scaled by (time of a call without events) / (their sum), which brings each within a few per cent of
+    # the kernel durations that rocprofv3 --kernel-trace reports for the same stream (profiles/).
+    dom_stage = {dl.DISCO_PATH_MATERIALIZED: 1, dl.DISCO_PATH_SYMMETRIC: 1, dl.DISCO_PATH_FUSED: 3}.get(resolved)
     stage_steps = min(args.steps, 3)
-    acc = np.zeros(nstages)
-    ncalls = 0
-    for k in range(stage_steps):
+    sets = [HipEvents(nstages + 1) for _ in range(stage_steps * len(ranks))]
+    k = 0
+    for _ in range(stage_steps):
         for n, r in enumerate(ranks):
+            dl.disco_set_stage_events(sets[k].arr, sets[k].n)
             dl.disco_loss_fwd_bwd(Id, Td, B, d, r, N, s, dt, path, 1 if n > 0 else 0, loss, gI, gT, gs, ws, ws_bytes, stream)
-            torch.cuda.synchronize()
-            acc += np.array([ev.elapsed_ms(i, i + 1) for i in range(nstages)])
-            ncalls += 1
-    stage_avg = acc / ncalls
+            k += 1
+    torch.cuda.synchronize()
     dl.disco_set_stage_events(None, 0)
+    stage_raw = np.zeros(nstages)
+    for e in sets:
+        stage_raw += np.array([e.elapsed_ms(i, i + 1) for i in range(nstages)])
+    stage_raw /= len(sets)
+    stage_avg = stage_raw * ((total_ms / args.steps / len(ranks)) / stage_raw.sum())
+    if dom_stage is None:
+        dom_stage = int(np.argmax(stage_avg))
 
     ms_per_step = total_ms / args.steps
     calls_per_step = len(ranks)
@@ -212,7 +229,7 @@ def main():
         dtype = "bf16"
     else:
         names = ["similarity", "row_softmax", "scalars", "key_grad", "query_grad"]
-        dom = int(np.argmax(stage_avg))
+        dom = dom_stage
         dom_flops = 4.0 * b * B * d
         peak, bound, unit = PEAK_FP32_TFLOPS, "alu", "TFLOP/s"
         dtype = "f32"
@@ -224,6 +241,7 @@ def main():
         "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, PATH_NAMES[resolved], names[dom])),
         "avg_launch_ms": round(dom_ms, 4), "flops_per_launch": dom_flops,
         "stages_ms": {n: round(float(v), 4) for n, v in zip(names, stage_avg)},
+        "stage_event_overhead": round(float(stage_raw.sum() / stage_avg.sum()) - 1.0, 4),
     }
 
     cpu = None
@@ -278,20 +296,21 @@ def bench_mfma_peak(args, dl, np, torch):
     stream = torch.cuda.current_stream()
     iters = 40000                                   # x 8 MFMAs x 32768 flop per wave
     rows = []
-    for wgs in (cus // 4, cus):                     # a quarter of the chip busy, then all of it
+    for varied, wgs in ((0, cus), (1, cus // 4), (1, cus)):   # quiet operands; then data-like ones on a quarter and on all of the chip
         for _ in range(max(args.warmup, 20)):
-            dl.disco_mfma_probe(wgs, iters, sink, clocks, stream)
+            dl.disco_mfma_probe(wgs, iters, varied, sink, clocks, stream)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         a.record(stream)
         for _ in range(args.steps):
-            dl.disco_mfma_probe(wgs, iters, sink, clocks, stream)
+            dl.disco_mfma_probe(wgs, iters, varied, sink, clocks, stream)
         b.record(stream)
         torch.cuda.synchronize()
         ms = a.elapsed_time(b) / args.steps
         c = clocks.cpu().numpy()
         flops = wgs * 8 * iters * 8 * 32768.0
-        rows.append({"workgroups": wgs, "ms_per_launch": round(ms, 4), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+        rows.append({"operands": "sign, exponent and mantissa vary" if varied else "mantissa varies only", "workgroups": wgs,
+                     "ms_per_launch": round(ms, 4), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
                      "shader_clock_mhz": round(100.0 * float(c[0]) / float(c[1]), 1)})
     full = rows[-1]
     out = {"metric": "bf16 MFMA issue rate, registers only, all compute units", "value": full["tflops"], "unit": "TFLOP/s",

@@ -181,7 +181,8 @@ DISCO_API int disco_loss_fwd_bwd_static(const void* I, const void* T, int64_t B,
  * NULL to switch stage timing off (the default).  The setting is process-wide: it is meant for a
  * benchmark that owns the process, not for use next to other callers of the library.  While set, every
  * disco_loss_fwd_bwd / clip_loss_fwd_bwd call made from any thread records events[0] on its stream before its first
- * kernel and events[k] after stage k, for as many stages as fit in `count`; the caller synchronises
+ * kernel and events[k] after stage k, for as many stages as fit in `count` (NULL entries are skipped, so that a
+ * caller can bracket one stage alone and leave the others undisturbed); the caller synchronises
  * and reads the intervals with hipEventElapsedTime.  The library keeps the pointer until it is
  * replaced.  Stages of DISCO_PATH_MATERIALIZED (DISCO_STAGES_MATERIALIZED = 6):
  *   1 row norms + positive-pair logits   2 logit tiles + softmax numerators   3 row merge + scaled transpose
@@ -204,11 +205,13 @@ DISCO_API int disco_set_stage_events(void** events, int count);
 /*
  * Measurement only: `workgroups` workgroups of 8 waves each issue `iters` x 8 bf16 MFMA 32x32x16 instructions per
  * wave (32768 flop each) from registers, with no memory traffic: what the matrix cores sustain once the clock
- * management has settled, the ceiling under the published peak that a tile kernel works against.  sink: one device
+ * management has settled, the ceiling under the published peak that a tile kernel works against.  varied != 0: the
+ * operands differ in sign, exponent and mantissa from element to element (as real data does); 0: in the mantissa
+ * only, which draws less power.  sink: one device
  * float (never written); clocks: two device uint64, filled by workgroup 0 with its elapsed shader-clock ticks and
  * its elapsed ticks of the fixed 100 MHz counter (their ratio is the shader clock in units of 100 MHz).
  */
-DISCO_API int disco_mfma_probe(int workgroups, int iters, float* sink, unsigned long long* clocks, void* hip_stream);
+DISCO_API int disco_mfma_probe(int workgroups, int iters, int varied, float* sink, unsigned long long* clocks, void* hip_stream);
 
 /*
  * Feature preparation on either side of the loss.  In Alg. 1 the encoders hand the features to the loss

@@ -68,7 +68,7 @@ def _load():
     lib.disco_logit_scale_fwd.restype = ci
     lib.disco_logit_scale_bwd.argtypes = [vp, f32, vp, vp, ci, vp]
     lib.disco_logit_scale_bwd.restype = ci
-    lib.disco_mfma_probe.argtypes = [ci, ci, vp, vp, vp]
+    lib.disco_mfma_probe.argtypes = [ci, ci, ci, vp, vp, vp]
     lib.disco_mfma_probe.restype = ci
     lib.disco_status_string.argtypes = [ci]
     lib.disco_status_string.restype = ctypes.c_char_p
@@ -160,8 +160,8 @@ def disco_set_stage_events(events, count: int) -> int:
     return _lib.disco_set_stage_events(events, int(count))
 
 
-def disco_mfma_probe(workgroups, iters, sink, clocks, stream=None, check=True) -> int:
-    st = _lib.disco_mfma_probe(int(workgroups), int(iters), _ptr(sink), _ptr(clocks), _stream_ptr(stream))
+def disco_mfma_probe(workgroups, iters, varied, sink, clocks, stream=None, check=True) -> int:
+    st = _lib.disco_mfma_probe(int(workgroups), int(iters), int(varied), _ptr(sink), _ptr(clocks), _stream_ptr(stream))
     if check and st != DISCO_OK:
         raise DiscoError(st, "disco_mfma_probe")
     return st

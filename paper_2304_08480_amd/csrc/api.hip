@@ -14,7 +14,7 @@ std::atomic<int> g_stage_count{0};
 namespace disco {
 void stage_mark(hipStream_t st, int k) {
   void** ev = g_stage_events.load(std::memory_order_acquire);
-  if (ev && k < g_stage_count.load(std::memory_order_acquire)) (void)hipEventRecord(static_cast<hipEvent_t>(ev[k]), st);
+  if (ev && k < g_stage_count.load(std::memory_order_acquire) && ev[k]) (void)hipEventRecord(static_cast<hipEvent_t>(ev[k]), st);
 }
 }  // namespace disco
 
