@@ -71,24 +71,29 @@ typedef enum { DISCO_F32 = 0, DISCO_BF16 = 1 } disco_dtype;
  * DISCO_PATH_MATERIALIZED bf16 MFMA tiles.  The logit blocks are computed once; the un-normalised
  *                         softmax numerators are kept in bf16 (2*b*B*2 bytes) and feed the two
  *                         gradient contractions (12*b*B*d flop).  Needs dtype bf16, d % 64 == 0,
- *                         b % 256 == 0, B <= 2^23.
+ *                         B <= 2^23.  A share b that is not a whole number of 256-row tiles is rounded up
+ *                         to one inside the workspace (zero-padded copies of I, T and the rank's rows,
+ *                         2*(B+b)*d*2 more bytes; the padding takes part in no softmax, sum or output),
+ *                         so the call costs what the rounded-up shape costs.
  * DISCO_PATH_FUSED        bf16 MFMA tiles, streaming: a forward pass keeps the row sums on chip and
  *                         writes nothing of size b x B; the backward pass recomputes the logits one
  *                         key panel (at most 16384 keys) at a time and contracts each panel while
  *                         it is cache-resident (16*b*B*d flop, workspace 2*b*W*2 bytes for panel
- *                         width W).  Same shape limits as MATERIALIZED.
+ *                         width W).  Shape limits of MATERIALIZED and b % 256 == 0.
  * DISCO_PATH_SYMMETRIC    bf16 MFMA tiles, N = 1 only (the non-decomposed loss, Eq. 1 / Fig. 1): the B x B
  *                         similarity matrix is computed once and serves both directions (text -> image is
  *                         its transpose); one matrix of numerators (B*B*2 bytes) against one exponent
  *                         reference, turned in place into the combined gradient matrix, then one contraction
- *                         per feature gradient: 6*B^2*d flop instead of 12.  Same shape limits as
- *                         MATERIALIZED.  Inputs whose rows' or columns' largest logits lie more than about
+ *                         per feature gradient: 6*B^2*d flop instead of 12.  Shape limits of MATERIALIZED
+ *                         and B % 256 == 0.  Inputs whose rows' or columns' largest logits lie more than about
  *                         60 (base 2) under the largest positive-pair logit are handed over, inside the same
  *                         call, to the MATERIALIZED kernels, so the workspace is sized for those as well.
- * DISCO_PATH_AUTO         the fastest path that supports the arguments: SYMMETRIC (N = 1) or MATERIALIZED
- *                         when their shape limits hold, else NAIVE.  Shares that are not a multiple of 256 pairs, feature
- *                         widths that are not a multiple of 64 and fp32 inputs therefore run on the vector
- *                         ALUs, an order of magnitude slower; disco_resolve_path tells which path a call takes.
+ * DISCO_PATH_AUTO         the fastest path that supports the arguments: SYMMETRIC (N = 1, B % 256 == 0) or
+ *                         MATERIALIZED when their shape limits hold, else NAIVE.  Feature widths that are not
+ *                         a multiple of 64, fp32 inputs, and ragged shares of blocks smaller than
+ *                         b*B = 2^18 logits (launch-bound either way) therefore run on the vector ALUs, for
+ *                         large shapes an order of magnitude slower; disco_resolve_path tells which path a
+ *                         call takes.
  */
 typedef enum {
   DISCO_PATH_AUTO = 0,
@@ -147,7 +152,7 @@ DISCO_API int clip_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t
  * gradient in the rank's own rows plus the key-side gradient in all B rows (the part Eq. 5 / Eq. 7 would send to
  * the other ranks).  Arguments, ownership, errors, paths, `accumulate`, stream and capture rules are those of
  * disco_loss_fwd_bwd, with one matrix Z for I and T and one gradient gZ; B odd is DISCO_ERR_SHAPE; the bf16 MFMA
- * paths additionally need (B/2) % 256 == 0.  ntxent_workspace_bytes / ntxent_resolve_path are this entry's
+ * paths additionally need (B/2) % 256 == 0 and b % 256 == 0.  ntxent_workspace_bytes / ntxent_resolve_path are this entry's
  * counterparts of disco_workspace_bytes / disco_resolve_path.
  */
 DISCO_API int ntxent_resolve_path(int64_t B, int64_t d, int32_t N, int dtype, int path);

@@ -37,6 +37,9 @@ int check_shape(int64_t B, int64_t d, int32_t N) {
   return DISCO_OK;
 }
 
+// smallest b x B block for which DISCO_PATH_AUTO sends a ragged bf16 share to the tile kernels
+constexpr int64_t RAGGED_MIN_BLOCK = (int64_t)256 * 1024;
+
 // 16-byte alignment of the feature matrices: the bf16 tile kernels fetch them in 16-byte pieces
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -45,18 +48,22 @@ int resolve(int64_t B, int64_t d, int32_t N, int dtype, int path, int variant = 
   if (st != DISCO_OK) return -st;
   if (variant == LOSS_NTXENT && B % 2 != 0) return -DISCO_ERR_SHAPE;       // two views of B/2 samples
   if (dtype != DISCO_F32 && dtype != DISCO_BF16) return -DISCO_ERR_UNSUPPORTED;
+  const bool tiles = mfma_supported(B, d, N, dtype, variant);          // the bf16 tile kernels can take it
+  const bool whole = tiles && mfma_whole_tiles(B, N);                  // without padding the share to 256-row tiles
   switch (path) {
     case DISCO_PATH_AUTO:
-      if (!mfma_supported(B, d, N, dtype, variant)) return DISCO_PATH_NAIVE;
-      return N == 1 && variant == LOSS_CLIP ? DISCO_PATH_SYMMETRIC : DISCO_PATH_MATERIALIZED;
+      if (whole) return N == 1 && variant == LOSS_CLIP ? DISCO_PATH_SYMMETRIC : DISCO_PATH_MATERIALIZED;
+      // a ragged share is padded to whole tiles: worth it once the padded block is more than a few tiles of work
+      // (below that the call is launch-bound on either path and the fp32 one has fewer launches)
+      return tiles && (B / N) * B >= RAGGED_MIN_BLOCK ? DISCO_PATH_MATERIALIZED : DISCO_PATH_NAIVE;
     case DISCO_PATH_NAIVE:
       return DISCO_PATH_NAIVE;
     case DISCO_PATH_MATERIALIZED:
-      return mfma_supported(B, d, N, dtype, variant) ? DISCO_PATH_MATERIALIZED : -DISCO_ERR_UNSUPPORTED;
+      return tiles ? DISCO_PATH_MATERIALIZED : -DISCO_ERR_UNSUPPORTED;
     case DISCO_PATH_FUSED:
-      return mfma_supported(B, d, N, dtype, variant) ? DISCO_PATH_FUSED : -DISCO_ERR_UNSUPPORTED;
+      return whole ? DISCO_PATH_FUSED : -DISCO_ERR_UNSUPPORTED;
     case DISCO_PATH_SYMMETRIC:
-      return N == 1 && variant == LOSS_CLIP && mfma_supported(B, d, N, dtype, variant) ? DISCO_PATH_SYMMETRIC : -DISCO_ERR_UNSUPPORTED;
+      return N == 1 && variant == LOSS_CLIP && whole ? DISCO_PATH_SYMMETRIC : -DISCO_ERR_UNSUPPORTED;
     default:
       return -DISCO_ERR_UNSUPPORTED;
   }

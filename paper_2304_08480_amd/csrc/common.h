@@ -50,7 +50,10 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 size_t naive_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant = LOSS_CLIP);
 int naive_run(const Problem& p);
 
+// the bf16 tile kernels can take the shape (materialized path; a rank share that is not a whole number of 256-row
+// tiles is zero-padded in the workspace) / the share is whole tiles (what the fused and symmetric paths need too)
 bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype, int variant = LOSS_CLIP);
+bool mfma_whole_tiles(int64_t B, int32_t N);
 size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant = LOSS_CLIP);
 int mfma_stored_run(const Problem& p);
 size_t mfma_fused_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant = LOSS_CLIP);

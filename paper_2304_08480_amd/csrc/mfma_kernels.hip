@@ -50,8 +50,8 @@ __device__ __forceinline__ bool xcd_linear(int total, int& lin) {
 
 // ------------------------------------------------------------------------------------------------
 struct BlockPtrs {
-  const uint16_t* X;     // b x d, the rank's rows
-  const uint16_t* Y;     // B x d
+  const uint16_t* X;     // b x d, the rank's rows (zero rows past the real ones)
+  const uint16_t* Y;     // B x d (zero rows past the real ones)
   uint16_t* E;           // b x W stored numerators of one key panel, in 64 x 64 blocks (e_index)
   float* lpart;          // (B/128) x b partial row sums (label column excluded)
   float* ediag;          // b: numerator of the label column
@@ -75,6 +75,9 @@ struct Blocks {
   int nblk;              // blocks in use: 2 for the CLIP loss, 1 for the two-view loss and for the symmetric full loss
   const int* gate;       // nullptr: the kernel always runs; else it runs only while *gate == gate_value (the symmetric
   int gate_value;        // full-loss path hands over to the two-block path through this flag)
+  int64_t rows, keys;    // the rank's rows and the batch as the caller has them.  The kernels' own b / B arguments are
+                         // these rounded up to whole 256-row tiles; where they differ (a ragged share), X and Y are
+                         // zero-padded copies, query rows >= rows and key columns >= keys are padding
 };
 
 __device__ __forceinline__ bool gated_off(const Blocks& bl) { return bl.gate != nullptr && *bl.gate != bl.gate_value; }
@@ -104,8 +107,9 @@ static_assert(NORM_BLOCKS == NTHREADS, "the logit kernel folds the partial maxim
 //  * the rest: positive-pair logit and query norm of every local row, one wave per (block, row); the first of
 //    these workgroups also clears the query-tile repair flags of both blocks.  The positive of local row i is
 //    key row label_row(rank b + i): the same global row for the CLIP loss, the other view's row for the two-view loss.
-__global__ __launch_bounds__(256) void k_prep(Blocks bl, const uint16_t* I, const uint16_t* T, int64_t B, int64_t b, int64_t d, int rank,
-                                              float s2, float* wgmax) {
+//    B, b: the real sizes; bp: b rounded up to whole tiles (the padding rows get a zero logit and a zero norm).
+__global__ __launch_bounds__(256) void k_prep(Blocks bl, const uint16_t* I, const uint16_t* T, int64_t B, int64_t b, int64_t bp, int64_t d,
+                                              int rank, float s2, float* wgmax) {
   if (gated_off(bl)) return;
   __shared__ float red[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -144,13 +148,17 @@ __global__ __launch_bounds__(256) void k_prep(Blocks bl, const uint16_t* I, cons
     if (threadIdx.x == 0) wgmax[which * NORM_BLOCKS + idx] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     return;
   }
-  const int64_t rb = (b + 3) / 4;                       // row workgroups per block
+  const int64_t rb = (bp + 3) / 4;                      // row workgroups per block
   const int64_t q = (int64_t)blockIdx.x - 2 * NORM_BLOCKS;
   if (q == 0)
-    for (int64_t it = threadIdx.x; it < b / BN; it += 256) { bl.z[0].tileflag[it] = 0; bl.z[1].tileflag[it] = 0; }
+    for (int64_t it = threadIdx.x; it < bp / BN; it += 256) { bl.z[0].tileflag[it] = 0; bl.z[1].tileflag[it] = 0; }
   const BlockPtrs& p = bl.z[q / rb];
   const int64_t i = (q % rb) * 4 + wave;
-  if (i >= b) return;
+  if (i >= bp) return;
+  if (i >= b) {
+    if (lane == 0) { p.zd2[i] = 0.f; p.xnorm[i] = 0.f; }
+    return;
+  }
   const uint16_t* x = p.X + i * d;
   const uint16_t* y = p.Y + label_row((int64_t)rank * b + i, B, bl.variant) * d;
   float dot = 0.f, nn = 0.f;
@@ -164,6 +172,27 @@ __global__ __launch_bounds__(256) void k_prep(Blocks bl, const uint16_t* I, cons
   if (lane == 0) { p.zd2[i] = s2 * dot; p.xnorm[i] = sqrtf(nn); }
 }
 
+// Operands of a ragged share (the rank's rows or the batch are not whole 256-row tiles): zero-padded copies of I and T
+// (Bp rows each) and of the rank's rows of both (bp rows each), so that the tile kernels read whole tiles of
+// memory that exists and the padding contributes exact zeros to every contraction.  16-byte pieces, grid-stride.
+__global__ __launch_bounds__(256) void k_pad_operands(const uint16_t* I, const uint16_t* T, int64_t B, int64_t Bp, int64_t b, int64_t bp,
+                                                      int64_t d, int rank, uint16_t* Ipad, uint16_t* Tpad, uint16_t* XI, uint16_t* XT) {
+  const int64_t cpr = d >> 3;                              // 16-byte pieces per row
+  const int64_t nY = Bp * cpr, nX = bp * cpr;
+  for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < 2 * (nY + nX); c += (int64_t)gridDim.x * 256) {
+    const int seg = c < nY ? 0 : c < 2 * nY ? 1 : c < 2 * nY + nX ? 2 : 3;
+    const int64_t w = c - (seg == 0 ? 0 : seg == 1 ? nY : seg == 2 ? 2 * nY : 2 * nY + nX);
+    const int64_t row = w / cpr, piece = w - row * cpr;
+    const uint16_t* src = (seg & 1) ? T : I;
+    uint16_t* dst = seg == 0 ? Ipad : seg == 1 ? Tpad : seg == 2 ? XI : XT;
+    const bool there = seg < 2 ? row < B : row < b;
+    const int64_t srow = seg < 2 ? row : (int64_t)rank * b + row;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (there) v = *reinterpret_cast<const u32x4*>(src + srow * d + piece * 8);
+    *reinterpret_cast<u32x4*>(dst + row * d + piece * 8) = v;
+  }
+}
+
 // Element (i, jl) of a stored numerator panel of width W: 64 x 64 blocks, block rows contiguous (format
 // FMT_KB / FMT_RB of mfma_tile.h).
 __device__ __forceinline__ int64_t e_index(int64_t i, int64_t jl, int64_t W) {
@@ -174,16 +203,20 @@ __device__ __forceinline__ int64_t e_index(int64_t i, int64_t jl, int64_t W) {
 // The numerators leave through LDS: each lane holds 4 consecutive key columns of 32 different query rows,
 // which as direct global stores would be 16-byte fragments; staged as a row-major 256 x 256 bf16 tile (8-byte
 // granules XOR-swizzled with the row: conflict-free 8-byte writes and 16-byte reads) they go out as whole
-// 512-byte row segments.  DIAG: the tile contains label columns, which are stored as 0 and kept in fp32 in ediag.
+// 512-byte row segments.  MASK_DIAG: the tile contains label columns, which are stored as 0 and kept in fp32 in ediag.
 // The label of query row i is key row lab0 + i; key row self0 + i is left out of row i's softmax (stored as 0, in
-// no sum; self0 far negative: no such column).  LOCAL (with STATS): the row sums and the label numerators are added
-// into rs / kept in ed (registers of the lane, indexed like ref2) instead of being written to lpart / ediag.
+// no sum; self0 far negative: no such column), and so are the padding columns from key row nkeys on (MASK_EDGE only:
+// the caller takes that variant for the tiles they fall into).  LOCAL (with STATS): the row sums and the label numerators
+// are added into rs / kept in ed (registers of the lane, indexed like ref2) instead of being written to lpart / ediag.
 constexpr int64_t NO_SELF = -((int64_t)1 << 40);
 
-template <bool STATS, bool STORE, bool DIAG, bool LOCAL = false>
+enum { MASK_NONE = 0, MASK_DIAG = 1, MASK_EDGE = 2 };     // MASK_EDGE: label / left-out columns and padding columns
+
+template <bool STATS, bool STORE, int MASK, bool LOCAL = false>
 __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)[4][2], char* smem, int64_t b, float s2, int64_t i0,
-                                               int64_t j0, int64_t lab0, int64_t self0, const float (&ref2)[2],
+                                               int64_t j0, int64_t lab0, int64_t self0, int64_t nkeys, const float (&ref2)[2],
                                                float* rs = nullptr, float* ed = nullptr) {
+  constexpr bool DIAG = MASK != MASK_NONE, EDGE = MASK == MASK_EDGE;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3, half = lane >> 5;
 #pragma unroll
@@ -197,6 +230,9 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
     const int dl = dl64 >= 0 && dl64 < 128 ? (int)dl64 : -1;
     const int64_t dm64 = self0 + i - (j0 + wm * 128 + half * 4);
     const int dm = dm64 >= 0 && dm64 < 128 ? (int)dm64 : -1;
+    // first padding column, relative like dl (128: none among this lane's columns)
+    const int64_t jl64 = nkeys - (j0 + wm * 128 + half * 4);
+    const int jlim = jl64 >= 128 ? 128 : jl64 > 0 ? (int)jl64 : 0;
     float rowsum = 0.f;
     char* lrow = smem + il * E_ROW_BYTES;
 #pragma unroll
@@ -217,7 +253,7 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
             }
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            if (dm == bm * 32 + q * 8 + r) e[r] = 0.f;
+            if (dm == bm * 32 + q * 8 + r || (EDGE && bm * 32 + q * 8 + r >= jlim)) e[r] = 0.f;
         }
         if (STATS) rowsum += (e[0] + e[1]) + (e[2] + e[3]);
         if (STORE) {
@@ -268,8 +304,11 @@ __device__ __forceinline__ void store_staged_numerators(const BlockPtrs& p, cons
 // keys (nothing of size b x B is written), then STORE-only passes that recompute one panel at a time.
 // A STATS pass derives the rows' exponent references (row_reference; k_row_merge records the same values in ref2);
 // a pass without STATS reads them from ref2, so that it sees the references a repair has replaced.
-template <bool STATS, bool STORE>
-__global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float s2,
+// b: the rank's rows rounded up to whole tiles; B: the key rows that exist (the panel widths cover them rounded up to
+// whole tiles); g0: global row of the rank's first row.  RAGGED: the last key tile may hold padding columns (the
+// instance without it keeps the tile walk free of that variant of the epilogue and of the registers it costs).
+template <bool STATS, bool STORE, bool RAGGED = false>
+__global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, int64_t B, int64_t d, int64_t g0, float s2,
                                                           int64_t jp0, int64_t W, int sbi, int sbj, int nblk) {
   if (gated_off(bl)) return;
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -337,12 +376,13 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
     mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
 
     // label of query row i is key row lab0 + i (one offset for the whole tile: tiles do not straddle the two views)
-    const int64_t lab0 = label_row((int64_t)rank * b + i0, B, bl.variant) - i0;
-    const int64_t self0 = bl.variant == LOSS_NTXENT ? (int64_t)rank * b : NO_SELF;
-    // Only the tiles that the label diagonal (or the left-out diagonal) crosses pay for finding those columns.
+    const int64_t lab0 = label_row(g0 + i0, B, bl.variant) - i0;
+    const int64_t self0 = bl.variant == LOSS_NTXENT ? g0 : NO_SELF;
+    // Only the tiles that the label diagonal (or the left-out diagonal) crosses, or that hold padding columns, pay
+    // for finding those columns.
     const bool diag = ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) || ((self0 + i0 < j0 + BM) && (j0 < self0 + i0 + BN));
-    if (diag) logit_epilogue<STATS, STORE, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, ref2);
-    else logit_epilogue<STATS, STORE, false>(p, acc, smem, b, s2, i0, j0, lab0, self0, ref2);
+    if (diag || (RAGGED && j0 + BM > B)) logit_epilogue<STATS, STORE, RAGGED ? MASK_EDGE : MASK_DIAG>(p, acc, smem, b, s2, i0, j0, lab0, self0, B, ref2);
+    else logit_epilogue<STATS, STORE, MASK_NONE>(p, acc, smem, b, s2, i0, j0, lab0, self0, B, ref2);
     if (STORE) store_staged_numerators(p, smem, i0, j0 - jp0, W);
   }
 }
@@ -393,6 +433,10 @@ __global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int np
   red[wave][lane] = (a0 + a1) + (a2 + a3);
   __syncthreads();
   if (wave != 0 || i >= b) return;
+  if (i >= bl.rows) {                                   // a padding row: no weight anywhere, no flag
+    p.ref2[i] = 0.f; p.beta[i] = 0.f; p.gdiag[i] = 0.f; p.ce[i] = 0.f;
+    return;
+  }
   float off = 0.f;
 #pragma unroll
   for (int w = 0; w < 16; w += 4) off += (red[w][lane] + red[w + 1][lane]) + (red[w + 2][lane] + red[w + 3][lane]);
@@ -426,8 +470,8 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
   if (p.tileflag[it] == 0) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3, half = lane >> 5;
   const int64_t i0 = (int64_t)it * BN;
-  const int64_t lab0 = label_row((int64_t)rank * b + i0, B, bl.variant) - i0;
-  const int64_t self0 = bl.variant == LOSS_NTXENT ? (int64_t)rank * b : NO_SELF;
+  const int64_t lab0 = label_row((int64_t)rank * bl.rows + i0, B, bl.variant) - i0;
+  const int64_t self0 = bl.variant == LOSS_NTXENT ? (int64_t)rank * bl.rows : NO_SELF;
   float* red = reinterpret_cast<float*>(smem);            // [2][256] exchange between the two key halves
   f32x16 acc[4][2];
   float ref2[2] = {-INFINITY, -INFINITY};
@@ -440,7 +484,10 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     mainloop<FMT_K, FMT_K, true>(p.Y + (int64_t)jt * BM * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
     const int64_t j0 = (int64_t)jt * BM;
-    const bool has_self = (self0 + i0 < j0 + BM) && (j0 < self0 + i0 + BN);   // the left-out column takes no part in the maximum
+    // the left-out column and the padding columns take no part in the maximum
+    const bool has_self = (self0 + i0 < j0 + BM) && (j0 < self0 + i0 + BN);
+    const int64_t jl64 = bl.keys - (j0 + wm * 128 + half * 4);
+    const int jlim = jl64 >= 128 ? 128 : jl64 > 0 ? (int)jl64 : 0;
 #pragma unroll
     for (int bn = 0; bn < 2; ++bn) {
       const int64_t dm64 = self0 + i0 + wn * 64 + bn * 32 + (lane & 31) - (j0 + wm * 128 + half * 4);
@@ -448,7 +495,8 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
       for (int bm = 0; bm < 4; ++bm)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const bool skip = has_self && dm64 == bm * 32 + (e >> 2) * 8 + (e & 3);
+          const int jl = bm * 32 + (e >> 2) * 8 + (e & 3);
+          const bool skip = (has_self && dm64 == jl) || jl >= jlim;
           ref2[bn] = skip ? ref2[bn] : fmaxf(ref2[bn], acc[bm][bn][e] * s2);
         }
     }
@@ -477,9 +525,10 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
-    const bool diag = ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) || ((self0 + i0 < j0 + BM) && (j0 < self0 + i0 + BN));
-    if (diag) logit_epilogue<true, STORE, true, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, ref2, rs, ed);
-    else logit_epilogue<true, STORE, false, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, ref2, rs, ed);
+    const bool diag = ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) || ((self0 + i0 < j0 + BM) && (j0 < self0 + i0 + BN)) ||
+                      j0 + BM > bl.keys;
+    if (diag) logit_epilogue<true, STORE, MASK_EDGE, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, bl.keys, ref2, rs, ed);
+    else logit_epilogue<true, STORE, MASK_NONE, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, bl.keys, ref2, rs, ed);
     if (STORE) store_staged_numerators(p, smem, i0, j0, B);
   }
   // row totals: the four lanes (two key halves x two lane halves) that share a row; exactly one of them met the label
@@ -500,7 +549,8 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
       const int il = wn * 64 + bn * 32 + lane;
       const float off = red[il] + red[256 + il], e = red[512 + il] + red[768 + il];
       p.ediag[i0 + il] = e;
-      row_outputs(p, i0 + il, off, e, off + e);
+      if (i0 + il < bl.rows) row_outputs(p, i0 + il, off, e, off + e);
+      else { p.beta[i0 + il] = 0.f; p.gdiag[i0 + il] = 0.f; p.ce[i0 + il] = 0.f; }
     }
   }
 }
@@ -546,7 +596,8 @@ __global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   const int ncols = d - k0 < BN ? (int)(d - k0) : BN;              // the last column tile may be partial (d % 64 == 0)
   mainloop<FMT_RB, FMT_K, true>(p.E + (jl0 >> 6) * 4096, (W >> 6) * 4096, p.Xs + k0 * b, b, (int)(b / BK), smem, acc, ncols);
-  store_tile_f32<ACCUMULATE>(acc, smem, p.gk + (jp0 + jl0) * d + k0, d, cs, ncols);
+  const int64_t left = bl.keys - (jp0 + jl0);                      // key rows that exist from this tile's first one on
+  store_tile_f32<ACCUMULATE>(acc, smem, p.gk + (jp0 + jl0) * d + k0, d, cs, ncols, left < BM ? (int)left : BM);
 }
 
 // Query-side products, split over the key index: part[ks][i][k] = sum_{j in split ks} E[i][j] y_jk.
@@ -603,7 +654,8 @@ __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b
 //            + cs gdiag^C_i T[lab]                                label-column term of block C's key side
 //   gT[lab] += cs (beta^C_i sum_ks part^C + gdiag^C_i I[lab]) + cs gdiag^A_i I[lab]
 // and the rows' shares of d/ds, <query-side vector, x_i>, per block.  One wave per row, fixed summation order.
-__global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int64_t b, int64_t d, int rank, float cs, int splitk) {
+// b: the real rows; bp: row pitch of the partial products.
+__global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int64_t b, int64_t bp, int64_t d, int rank, float cs, int splitk) {
   if (gated_off(bl)) return;
   typedef __attribute__((ext_vector_type(4))) float f32x4;
   const BlockPtrs& pa = bl.z[0];
@@ -617,8 +669,8 @@ __global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int64_t b, in
   for (int64_t k = lane * 4; k < d; k += 256) {
     f32x4 ua = {0.f, 0.f, 0.f, 0.f}, uc = {0.f, 0.f, 0.f, 0.f};
     for (int ks = 0; ks < splitk; ++ks) {
-      ua += *reinterpret_cast<const f32x4*>(pa.part + ((int64_t)ks * b + i) * d + k);
-      uc += *reinterpret_cast<const f32x4*>(pc.part + ((int64_t)ks * b + i) * d + k);
+      ua += *reinterpret_cast<const f32x4*>(pa.part + ((int64_t)ks * bp + i) * d + k);
+      uc += *reinterpret_cast<const f32x4*>(pc.part + ((int64_t)ks * bp + i) * d + k);
     }
     const u32x2 iw = *reinterpret_cast<const u32x2*>(pa.X + i * d + k);        // I[lab]
     const u32x2 tw = *reinterpret_cast<const u32x2*>(pc.X + i * d + k);        // T[lab]
@@ -773,8 +825,8 @@ __global__ __launch_bounds__(NTHREADS) void k_sym_logit(Blocks bl, int64_t B, in
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
     // the label of query row i is key row i: only the tiles on the diagonal contain label columns
-    if (it == jt) logit_epilogue<true, true, true>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, ref2);
-    else logit_epilogue<true, true, false>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, ref2);
+    if (it == jt) logit_epilogue<true, true, MASK_DIAG>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, B, ref2);
+    else logit_epilogue<true, true, MASK_NONE>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, B, ref2);
     lds_barrier();
     const int t = threadIdx.x;
     const int chunk16 = t & 31, r0 = t >> 5;
@@ -881,12 +933,14 @@ __global__ __launch_bounds__(256) void k_sym_finalize(Blocks bl, int64_t B, int6
 constexpr int NROWARRAYS = 7;
 
 struct Plan {
-  int64_t b, B, d;
+  int64_t b, B, d;       // b and B rounded up to whole 256-row tiles: what the tile kernels and the layout below see
+  int64_t b_real, B_real;
+  bool ragged;           // b or B was rounded up: the kernels read zero-padded copies of the operands (off_pad)
   int64_t W;             // key panel width (B for the materialized path)
   int npanels;
   int nparts;            // B / 128
   int nMq, nN, splitk, ktps;
-  size_t off_E, off_lpart, off_rows, off_Xs, off_part, off_ymax, off_flags, off_ref, total;
+  size_t off_E, off_lpart, off_rows, off_Xs, off_part, off_ymax, off_flags, off_ref, off_pad, total;
   size_t rows_stride;    // bytes of one b-float row array (aligned)
 };
 
@@ -900,7 +954,11 @@ int fused_panels(int64_t B) {
 
 Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused, int nblk = 2) {
   Plan pl;
-  pl.B = B; pl.d = d; pl.b = B / N;
+  pl.B_real = B; pl.b_real = B / N; pl.d = d;
+  pl.b = (pl.b_real + BN - 1) / BN * BN;
+  pl.B = (B + BM - 1) / BM * BM;
+  pl.ragged = pl.b != pl.b_real || pl.B != pl.B_real;
+  B = pl.B;
   const int64_t b = pl.b;
   pl.npanels = fused ? fused_panels(B) : 1;
   pl.W = B / pl.npanels;
@@ -933,6 +991,8 @@ Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused, int nblk = 2) {
   pl.off_ymax = o;   o += align_up((size_t)2 * NORM_BLOCKS * 4);         // partial maxima of the row norms
   pl.off_flags = o;  o += 2 * align_up((size_t)(b / BN) * 4);            // repair flags, one per query tile
   pl.off_ref = o;    o += 2 * pl.rows_stride;                            // exponent references of the rows
+  pl.off_pad = o;                                                        // padded I, T, I_r, T_r of a ragged share
+  if (pl.ragged) o += 2 * align_up((size_t)B * d * 2) + 2 * align_up((size_t)b * d * 2);
   pl.total = o;
   return pl;
 }
@@ -953,30 +1013,39 @@ bool allow_lds(K kernel, int bytes) {
 int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_value = 0, bool marks = true) {
   // the tile kernels use more LDS than the default limit; raised once per process (one device per process here)
   static const bool lds_ok = allow_lds(k_logit_tiles<true, true>, LOGIT_SMEM_BYTES) && allow_lds(k_logit_tiles<true, false>, LOGIT_SMEM_BYTES) &&
-                             allow_lds(k_logit_tiles<false, true>, LOGIT_SMEM_BYTES) && allow_lds(k_logit_repair<false>, LOGIT_SMEM_BYTES) &&
+                             allow_lds(k_logit_tiles<false, true>, LOGIT_SMEM_BYTES) && allow_lds(k_logit_tiles<true, true, true>, LOGIT_SMEM_BYTES) &&
+                             allow_lds(k_logit_repair<false>, LOGIT_SMEM_BYTES) &&
                              allow_lds(k_logit_repair<true>, LOGIT_SMEM_BYTES) && allow_lds(k_key_grad<false>, GEMM_SMEM_BYTES) &&
                              allow_lds(k_key_grad<true>, GEMM_SMEM_BYTES) && allow_lds(k_query_partial<false>, GEMM_SMEM_BYTES) &&
                              allow_lds(k_query_partial<true>, GEMM_SMEM_BYTES);
   if (!lds_ok) return DISCO_ERR_HIP;
   const int nblk = loss_blocks(pr.variant);
   const Plan pl = make_plan(pr.B, pr.d, pr.N, fused, nblk);
+  if (pl.ragged && (fused || pr.variant != LOSS_CLIP)) return DISCO_ERR_UNSUPPORTED;   // (the dispatch does not send these here)
   const int persistent_wgs = compute_units();
-  const int64_t b = pl.b, B = pl.B, d = pl.d, W = pl.W;
+  const int64_t b = pl.b, B = pl.B, d = pl.d, W = pl.W;     // whole tiles; the real sizes are pl.b_real, pl.B_real
   char* ws = static_cast<char*>(pr.ws);
   const uint16_t* I = static_cast<const uint16_t*>(pr.I);
   const uint16_t* T = static_cast<const uint16_t*>(pr.T);
   float* wgmax = reinterpret_cast<float*>(ws + pl.off_ymax);   // NORM_BLOCKS partial maxima of |I_j|^2, then of |T_j|^2
 
+  uint16_t* Ipad = reinterpret_cast<uint16_t*>(ws + pl.off_pad);
+  uint16_t* Tpad = reinterpret_cast<uint16_t*>(ws + pl.off_pad + align_up((size_t)B * d * 2));
+  uint16_t* XIpad = reinterpret_cast<uint16_t*>(ws + pl.off_pad + 2 * align_up((size_t)B * d * 2));
+  uint16_t* XTpad = reinterpret_cast<uint16_t*>(ws + pl.off_pad + 2 * align_up((size_t)B * d * 2) + align_up((size_t)b * d * 2));
+
   Blocks bl;
   bl.variant = pr.variant;
   bl.nblk = nblk;
+  bl.rows = pl.b_real;
+  bl.keys = pl.B_real;
   bl.gate = gate;
   bl.gate_value = gate_value;
   for (int z = 0; z < 2; ++z) {
     BlockPtrs& p = bl.z[z];
     const uint16_t* Xfull = z == 0 ? I : T;
-    p.X = Xfull + (size_t)pr.rank * b * d;
-    p.Y = z == 0 ? T : I;
+    p.X = pl.ragged ? (z == 0 ? XIpad : XTpad) : Xfull + (size_t)pr.rank * b * d;
+    p.Y = pl.ragged ? (z == 0 ? Tpad : Ipad) : (z == 0 ? T : I);
     p.E = reinterpret_cast<uint16_t*>(ws + pl.off_E + z * align_up((size_t)b * W * 2));
     p.lpart = reinterpret_cast<float*>(ws + pl.off_lpart + z * align_up((size_t)pl.nparts * b * 4));
     char* rows = ws + pl.off_rows + (size_t)z * NROWARRAYS * pl.rows_stride;
@@ -997,7 +1066,7 @@ int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_
   }
 
   const float s2 = pr.s * LOG2E;
-  const float c = loss_norm(B, pr.variant);
+  const float c = loss_norm(pl.B_real, pr.variant);
   const float cs = c * pr.s;
   hipStream_t st = pr.stream;
   const int nI = (int)(b / BN);
@@ -1018,19 +1087,23 @@ int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_
   const int qT = pl.nMq * pl.nN, qS = nblk * pl.splitk;
   const int q_wgs = qS % 8 == 0 ? 8 * qT * (qS / 8) : 8 % qS == 0 ? 8 * ((qT + 8 / qS - 1) / (8 / qS)) : (qS * qT + 7) / 8 * 8;
   const dim3 q_grid((unsigned)q_wgs);
+  const int64_t g0 = (int64_t)pr.rank * pl.b_real;       // global row of the rank's first row
   int stage = 0;
 
   if (marks) stage_mark(st, stage++);
-  k_prep<<<dim3((unsigned)(2 * NORM_BLOCKS + nblk * ((b + 3) / 4))), 256, 0, st>>>(bl, I, T, B, b, d, pr.rank, s2, wgmax);
+  if (pl.ragged)
+    k_pad_operands<<<dim3((unsigned)(8 * persistent_wgs)), 256, 0, st>>>(I, T, pl.B_real, B, pl.b_real, b, d, pr.rank, Ipad, Tpad, XIpad, XTpad);
+  k_prep<<<dim3((unsigned)(2 * NORM_BLOCKS + nblk * ((b + 3) / 4))), 256, 0, st>>>(bl, I, T, pl.B_real, pl.b_real, b, d, pr.rank, s2, wgmax);
   if (marks) stage_mark(st, stage++);
 
   int sbj;
   if (fused) {
     const dim3 g = logit_grid(B, sbj);
-    k_logit_tiles<true, false><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, sbi, sbj, nblk);
+    k_logit_tiles<true, false><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, pl.B_real, d, g0, s2, 0, B, sbi, sbj, nblk);
   } else {
     const dim3 g = logit_grid(B, sbj);
-    k_logit_tiles<true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, 0, B, sbi, sbj, nblk);
+    if (pl.ragged) k_logit_tiles<true, true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, pl.B_real, d, g0, s2, 0, B, sbi, sbj, nblk);
+    else k_logit_tiles<true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, pl.B_real, d, g0, s2, 0, B, sbi, sbj, nblk);
   }
   if (marks) stage_mark(st, stage++);
   k_row_merge<<<dim3((unsigned)((b + 63) / 64), (unsigned)nblk), 1024, 0, st>>>(bl, b, pl.nparts, pl.nparts, s2, nullptr, nullptr);
@@ -1043,7 +1116,7 @@ int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_
     const int64_t jp0 = (int64_t)pnl * W;
     if (fused) {
       const dim3 g = logit_grid(W, sbj);
-      k_logit_tiles<false, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2, jp0, W, sbi, sbj, nblk);
+      k_logit_tiles<false, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, pl.B_real, d, g0, s2, jp0, W, sbi, sbj, nblk);
     }
     if (pr.accumulate)
       k_key_grad<true><<<key_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, cs, jp0, W, nMk, pl.nN);
@@ -1057,8 +1130,8 @@ int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_
   }
   if (marks) stage_mark(st, stage++);
   if (pr.variant == LOSS_NTXENT) k_query_finalize_ntxent<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, b, B, d, pr.rank, cs, pl.splitk);
-  else k_query_finalize<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, b, d, pr.rank, cs, pl.splitk);
-  k_scalars<<<1, 1024, 0, st>>>(bl, b, c, pr.accumulate, pr.loss, pr.gs);
+  else k_query_finalize<<<dim3((unsigned)((pl.b_real + 3) / 4)), 256, 0, st>>>(bl, pl.b_real, b, d, pr.rank, cs, pl.splitk);
+  k_scalars<<<1, 1024, 0, st>>>(bl, pl.b_real, c, pr.accumulate, pr.loss, pr.gs);
   if (marks) stage_mark(st, stage++);
   return hipGetLastError() == hipSuccess ? DISCO_OK : DISCO_ERR_HIP;
 }
@@ -1087,6 +1160,8 @@ int mfma_sym_run_impl(const Problem& pr) {
   Blocks bl;
   bl.variant = LOSS_CLIP;
   bl.nblk = 1;
+  bl.rows = B;
+  bl.keys = B;
   bl.gate = nullptr;
   bl.gate_value = 0;
   BlockPtrs& p = bl.z[0];
@@ -1139,7 +1214,7 @@ int mfma_sym_run_impl(const Problem& pr) {
   int stage = 0;
 
   stage_mark(st, stage++);
-  k_prep<<<dim3((unsigned)(2 * NORM_BLOCKS + (B + 3) / 4)), 256, 0, st>>>(bl, I, T, B, B, d, 0, s2, wgmax);
+  k_prep<<<dim3((unsigned)(2 * NORM_BLOCKS + (B + 3) / 4)), 256, 0, st>>>(bl, I, T, B, B, B, d, 0, s2, wgmax);
   k_sym_ref<<<1, 1024, 0, st>>>(p.zd2, B, wgmax, s2, rglobal, gate);
   stage_mark(st, stage++);
   k_sym_logit<<<logit_grid, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, B, d, s2, rglobal, sbi, sbj);
@@ -1175,12 +1250,14 @@ bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype, int variant) {
   if (N <= 0 || B % N != 0) return false;
   const int64_t b = B / N;
   // two-view loss: a 256-row query tile must lie within one view, so that its labels are one offset away
-  if (variant == LOSS_NTXENT && (B % 2 != 0 || (B / 2) % 256 != 0)) return false;
+  if (variant == LOSS_NTXENT && (B % 2 != 0 || (B / 2) % 256 != 0 || b % 256 != 0)) return false;
   // per-lane load offsets are 32-bit byte offsets inside one operand tile: 256 rows of pitch b (Xs) or four block
   // rows of pitch 64 W (blocked numerators) must stay below 4 GiB
-  if (B > ((int64_t)1 << 23) || b > ((int64_t)1 << 22)) return false;
-  return b % 256 == 0 && d % 64 == 0;
+  if (B > ((int64_t)1 << 23) || b > ((int64_t)1 << 22)) return false;      // (rounding up to whole tiles stays within them)
+  return d % 64 == 0;
 }
+
+bool mfma_whole_tiles(int64_t B, int32_t N) { return N > 0 && B % N == 0 && (B / N) % 256 == 0; }
 
 size_t mfma_stored_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant) { return make_plan(B, d, N, false, loss_blocks(variant)).total; }
 size_t mfma_fused_workspace_bytes(int64_t B, int64_t d, int32_t N, int variant) { return make_plan(B, d, N, true, loss_blocks(variant)).total; }

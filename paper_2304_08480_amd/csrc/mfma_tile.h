@@ -296,12 +296,12 @@ __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A, int64_t
 // every global store is a full 1 KiB row segment (the accumulator layout would give 4-byte elements per
 // lane).  Two passes of 128 rows; LDS rows padded to 1056 bytes so that the two half-waves of a 4-byte
 // write land on different banks.  out points at the tile's first element; value = scale * acc (+ old);
-// only the first ncols columns (a multiple of 4) are touched.
+// only the first ncols columns (a multiple of 4) of the first nrows rows are touched.
 constexpr int OUT_ROW_BYTES = BN * 4 + 32;
 constexpr int OUT_SMEM_BYTES = 128 * OUT_ROW_BYTES;       // 132 KiB
 
-template <bool ACCUMULATE>
-__device__ __forceinline__ void store_tile_f32(f32x16 (&acc)[4][2], char* smem, float* out, int64_t ld, float scale, int ncols = BN) {
+template <bool ACCUMULATE, bool ROWMASK>
+__device__ __forceinline__ void store_tile_f32_rows(f32x16 (&acc)[4][2], char* smem, float* out, int64_t ld, float scale, int ncols, int nrows) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 2, wn = wave & 3, half = lane >> 5;
   const int chunk = t & 63, r0 = t >> 6;
@@ -313,7 +313,8 @@ __device__ __forceinline__ void store_tile_f32(f32x16 (&acc)[4][2], char* smem, 
     f32x4 old[8];
     if (ACCUMULATE && live) {
 #pragma unroll
-      for (int r = 0; r < 8; ++r) old[r] = *reinterpret_cast<const f32x4*>(out + (int64_t)(h * 128 + r * 8 + r0) * ld + chunk * 4);
+      for (int r = 0; r < 8; ++r)
+        if (!ROWMASK || h * 128 + r * 8 + r0 < nrows) old[r] = *reinterpret_cast<const f32x4*>(out + (int64_t)(h * 128 + r * 8 + r0) * ld + chunk * 4);
     }
     lds_barrier();
     if (wm == h) {
@@ -336,16 +337,26 @@ __device__ __forceinline__ void store_tile_f32(f32x16 (&acc)[4][2], char* smem, 
       for (int r = 0; r < 8; ++r) v[r] = *reinterpret_cast<const f32x4*>(smem + ((q * 8 + r) * 8 + r0) * OUT_ROW_BYTES + chunk * 16);
       if (ACCUMULATE && q == 1 && live) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) old[r] = *reinterpret_cast<const f32x4*>(out + (int64_t)(h * 128 + (8 + r) * 8 + r0) * ld + chunk * 4);
+        for (int r = 0; r < 8; ++r)
+          if (!ROWMASK || h * 128 + (8 + r) * 8 + r0 < nrows) old[r] = *reinterpret_cast<const f32x4*>(out + (int64_t)(h * 128 + (8 + r) * 8 + r0) * ld + chunk * 4);
       }
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
+        const bool there = live && (!ROWMASK || h * 128 + (q * 8 + r) * 8 + r0 < nrows);
         float* g = out + (int64_t)(h * 128 + (q * 8 + r) * 8 + r0) * ld + chunk * 4;
-        if (ACCUMULATE && live) v[r] += old[r];
-        if (live) *reinterpret_cast<f32x4*>(g) = v[r];
+        if (ACCUMULATE && there) v[r] += old[r];
+        if (there) *reinterpret_cast<f32x4*>(g) = v[r];
       }
     }
   }
+}
+
+// (a tile whose rows all exist takes the instance without the per-row tests)
+template <bool ACCUMULATE>
+__device__ __forceinline__ void store_tile_f32(f32x16 (&acc)[4][2], char* smem, float* out, int64_t ld, float scale, int ncols = BN,
+                                               int nrows = BM) {
+  if (nrows >= BM) store_tile_f32_rows<ACCUMULATE, false>(acc, smem, out, ld, scale, ncols, nrows);
+  else store_tile_f32_rows<ACCUMULATE, true>(acc, smem, out, ld, scale, ncols, nrows);
 }
 
 }  // namespace tile

@@ -174,6 +174,8 @@ CONFIGS: Dict[str, WorkloadConfig] = {
     "b64k_d768_n8": WorkloadConfig("b64k_d768_n8", 65536, 768, 8, "bf16", 1.0 / 0.07, 3, hard_frac=0.10),
     # the shape of the paper's own timing table (Table 4: 64 GPUs, batch 32,768, 512 pairs per GPU)
     "b32k_n64": WorkloadConfig("b32k_n64", 32768, 512, 64, "bf16", 1.0 / 0.07, 1),
+    # a batch whose rank share is not a whole number of 256-row tiles (3750 pairs per rank)
+    "b30k_n8_ragged": WorkloadConfig("b30k_n8_ragged", 30000, 512, 8, "bf16", 1.0 / 0.07, 5),
     # the batch of the paper's accuracy tables (Tables 5-7: 65,536 on 64 GPUs)
     "b64k_n64": WorkloadConfig("b64k_n64", 65536, 512, 64, "bf16", 1.0 / 0.07, 4),
 }

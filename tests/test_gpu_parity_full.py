@@ -4,8 +4,8 @@ entry against the float64 oracle.
 b32k_n8 (B=32768, d=512, N=8, bf16): two ranks dense against the per-rank oracle; the 8-rank accumulation and
 the non-decomposed entry point (full_n1, both bf16 paths) dense against the oracle of the original loss (Eq. 1).
 The larger workloads (B=196608 / N=64 at s=100, its weak-positive variant, B=65536 / d=768 / N=8 with
-near-duplicate rows, and the paper's own shapes B=32768 and 65536 on 64 ranks): one rank dense against the
-per-rank oracle, d/ds included.  The float64 references of one workload are computed once per session.
+near-duplicate rows, the paper's own shapes B=32768 and 65536 on 64 ranks, and a batch of 30000 on 8 ranks, whose
+3750-pair shares are not whole tiles): one rank dense against the per-rank oracle, d/ds included.  The float64 references of one workload are computed once per session.
 """
 import functools
 import time
@@ -97,7 +97,7 @@ def test_full_n1_against_the_full_loss(path):
 
 
 @pytest.mark.parametrize("name,rank", [("b196k_n64", 37), ("b196k_n64_hard", 63), ("b64k_d768_n8", 2),
-                                       ("b32k_n64", 41), ("b64k_n64", 0)])
+                                       ("b32k_n64", 41), ("b64k_n64", 0), ("b30k_n8_ragged", 7)])
 def test_large_workloads_dense(name, rank):
     cfg, I, T, run = _setup(name)
     print(f"case {name} B={cfg.B} d={cfg.d} N={cfg.N} rank={rank} s={cfg.s}", flush=True)
