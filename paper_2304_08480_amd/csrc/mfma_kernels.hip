@@ -48,6 +48,19 @@ __device__ __forceinline__ bool xcd_linear(int total, int& lin) {
   return (w >> 3) < chunk && lin < total;
 }
 
+// Tile (it, jt) at position lin of the walk over super-blocks of sbi query tiles x sbj key tiles: bands of sbj key
+// tiles one after the other, inside a band the super-blocks along the query tiles, inside a super-block the query
+// tile runs fastest.  The last super-block of either direction may be partial.
+__device__ __forceinline__ void superblock_tile(int lin, int nI, int nJ, int sbi, int sbj, int& it, int& jt) {
+  const int band = sbj * nI;
+  const int jb = lin / band, r = lin - jb * band;
+  const int hj = nJ - jb * sbj < sbj ? nJ - jb * sbj : sbj;
+  const int ib = r / (sbi * hj), r2 = r - ib * sbi * hj;
+  const int wi = nI - ib * sbi < sbi ? nI - ib * sbi : sbi;
+  it = ib * sbi + r2 % wi;
+  jt = jb * sbj + r2 / wi;
+}
+
 // ------------------------------------------------------------------------------------------------
 struct BlockPtrs {
   const uint16_t* X;     // b x d, the rank's rows (zero rows past the real ones)
@@ -317,8 +330,8 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
   // workgroup per tile would expose that latency and the launch of the next workgroup once per tile; here a
   // tile's stores drain while the next tile's operands are fetched.  gridDim.x is a multiple of 8, so a
   // workgroup stays on one XCD's contiguous eighth of the tile list.  The list runs over super-blocks of
-  // sbi query tiles x sbj key tiles (sbi divides the query tiles, sbj the key tiles, sbi sbj <= 32; 8 x 4 where
-  // the shape allows): the workgroups an XCD runs at one time then share sbi + sbj operand tiles in its L2.
+  // sbi query tiles x sbj key tiles (sbi sbj <= 32; 8 x 4 where the shape allows, see superblock_tile): the
+  // workgroups an XCD runs at one time then share sbi + sbj operand tiles in its L2.
   const int nI = (int)(b / BN), nJ = (int)(W / BM);
   const int total = nI * nJ;
   const int chunk = (total + 7) >> 3, padded = chunk << 3;
@@ -349,10 +362,8 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
     const BlockPtrs& p = bl.z[z];
     const int lin = (u & 7) * chunk + (u >> 3);
     if ((u >> 3) >= chunk || lin >= total) continue;                  // padding of the eighths (workgroup-uniform)
-    const int sbsz = sbi * sbj, sb = lin / sbsz, within = lin % sbsz;
-    const int nSBi = nI / sbi;
-    const int it = (sb % nSBi) * sbi + within % sbi;
-    const int jt = (sb / nSBi) * sbj + within / sbi;
+    int it, jt;
+    superblock_tile(lin, nI, nJ, sbi, sbj, it, jt);
     const int64_t i0 = (int64_t)it * BN, j0 = jp0 + (int64_t)jt * BM;
 
     // exponent reference of this lane's two query rows, fetched before the main loop so that the loads are
@@ -811,10 +822,8 @@ __global__ __launch_bounds__(NTHREADS) void k_sym_logit(Blocks bl, int64_t B, in
   for (int u = blockIdx.x; u < padded; u += gridDim.x) {
     const int lin = (u & 7) * chunk + (u >> 3);
     if ((u >> 3) >= chunk || lin >= total) continue;
-    const int sbsz = sbi * sbj, sb = lin / sbsz, within = lin % sbsz;
-    const int nSBi = nI / sbi;
-    const int it = (sb % nSBi) * sbi + within % sbi;
-    const int jt = (sb / nSBi) * sbj + within / sbi;
+    int it, jt;
+    superblock_tile(lin, nI, nJ, sbi, sbj, it, jt);
     const int64_t i0 = (int64_t)it * BN, j0 = (int64_t)jt * BM;
     f32x16 acc[4][2];
 #pragma unroll
@@ -997,6 +1006,15 @@ Plan make_plan(int64_t B, int64_t d, int32_t N, bool fused, int nblk = 2) {
   return pl;
 }
 
+// Query tiles per super-block of the logit tile walk (superblock_tile): the largest power of two <= 8 that divides
+// the query tiles where that is at least 4 (or all of them), else up to 8 with a partial last super-block.
+int superblock_width(int nI) {
+  int sbi = 8;
+  while (nI % sbi) sbi >>= 1;
+  if (sbi < 4 && sbi < nI) sbi = nI < 8 ? nI : 8;
+  return sbi;
+}
+
 // Compute units of the current device rounded down to a multiple of 8 (one persistent workgroup each).
 int compute_units() {
   int dev = 0, n = 0;
@@ -1070,14 +1088,11 @@ int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_
   const float cs = c * pr.s;
   hipStream_t st = pr.stream;
   const int nI = (int)(b / BN);
-  // super-block shape of the logit tile walk: the largest power of two <= 8 dividing the query tiles, then the
-  // largest power of two dividing the key tiles that keeps the super-block within 32 tiles
-  int sbi = 8;
-  while (nI % sbi) sbi >>= 1;
+  // super-block shape of the logit tile walk: sbi query tiles, then as many key tiles as keep it within 32 tiles
+  const int sbi = superblock_width(nI);
   auto logit_grid = [&](int64_t keys, int& sbj) {
     const int nJ = (int)(keys / BM);
-    sbj = 32 / sbi;
-    while (nJ % sbj) sbj >>= 1;
+    sbj = 32 / sbi < nJ ? 32 / sbi : nJ;
     const int tiles2 = nblk * ((nI * nJ + 7) / 8 * 8);  // every block, each padded to a multiple of 8
     return dim3((unsigned)(tiles2 < persistent_wgs ? tiles2 : persistent_wgs));
   };
@@ -1202,10 +1217,8 @@ int mfma_sym_run_impl(const Problem& pr) {
   const float cs = c * pr.s;
   hipStream_t st = pr.stream;
   const int nT = (int)(B / BN);
-  int sbi = 8;
-  while (nT % sbi) sbi >>= 1;
-  int sbj = 32 / sbi;
-  while (nT % sbj) sbj >>= 1;
+  const int sbi = superblock_width(nT);
+  const int sbj = 32 / sbi < nT ? 32 / sbi : nT;
   const int tiles = (nT * nT + 7) / 8 * 8;
   const dim3 logit_grid((unsigned)(tiles < persistent_wgs ? tiles : persistent_wgs));
   const dim3 key_grid((unsigned)(((nT * pl.nN + 7) / 8) * 8), 1);
