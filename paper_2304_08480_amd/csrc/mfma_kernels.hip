@@ -65,7 +65,7 @@ __device__ __forceinline__ void superblock_tile(int lin, int nI, int nJ, int sbi
 struct BlockPtrs {
   const uint16_t* X;     // b x d, the rank's rows (zero rows past the real ones)
   const uint16_t* Y;     // B x d (zero rows past the real ones)
-  uint16_t* E;           // b x W stored numerators of one key panel, in 64 x 64 blocks (e_index)
+  uint16_t* E;           // b x W stored numerators of one key panel, in 16-byte atoms (e_index)
   float* lpart;          // (B/128) x b partial row sums (label column excluded)
   float* ediag;          // b: numerator of the label column
   float* zd2;            // b: z2 of the positive pair
@@ -206,29 +206,35 @@ __global__ __launch_bounds__(256) void k_pad_operands(const uint16_t* I, const u
   }
 }
 
-// Element (i, jl) of a stored numerator panel of width W: 64 x 64 blocks, block rows contiguous (format
-// FMT_KB / FMT_RB of mfma_tile.h).
+// Element (i, jl) of a stored numerator panel of width W: 16-byte atoms of 8 consecutive keys, by groups of 64 query
+// rows, inside a group key piece by key piece (formats FMT_KA / FMT_RA of mfma_tile.h).
 __device__ __forceinline__ int64_t e_index(int64_t i, int64_t jl, int64_t W) {
-  return ((i >> 6) * (W >> 6) + (jl >> 6)) * 4096 + (i & 63) * 64 + (jl & 63);
+  return ((i >> 6) * (W >> 3) + (jl >> 3)) * 512 + (i & 63) * 8 + (jl & 7);
 }
 
-// Epilogue of one logit tile: numerators from the accumulators, row sums, staging of the bf16 tile in LDS.
-// The numerators leave through LDS: each lane holds 4 consecutive key columns of 32 different query rows,
-// which as direct global stores would be 16-byte fragments; staged as a row-major 256 x 256 bf16 tile (8-byte
-// granules XOR-swizzled with the row: conflict-free 8-byte writes and 16-byte reads) they go out as whole
-// 512-byte row segments.  MASK_DIAG: the tile contains label columns, which are stored as 0 and kept in fp32 in ediag.
+// Epilogue of one logit tile: numerators from the accumulators, row sums, the bf16 numerators to memory.
+// Each lane holds, per accumulator quad, 4 consecutive key columns of one query row, lanes l and l + 32 the two
+// halves of 8 consecutive keys; one v_permlane32_swap per register pair gives the lower lane the whole atom of an
+// even key piece and the upper lane that of the odd piece next to it, and the 32 lanes of a half-wave (32
+// consecutive query rows) then store 512 contiguous bytes of the panel (see e_index): no LDS, no barrier, so
+// the waves of a workgroup need not meet between the main loops of consecutive tiles.
+// MASK_DIAG: the tile contains label columns, which are stored as 0 and kept in fp32 in ediag.
 // The label of query row i is key row lab0 + i; key row self0 + i is left out of row i's softmax (stored as 0, in
 // no sum; self0 far negative: no such column), and so are the padding columns from key row nkeys on (MASK_EDGE only:
 // the caller takes that variant for the tiles they fall into).  LOCAL (with STATS): the row sums and the label numerators
 // are added into rs / kept in ed (registers of the lane, indexed like ref2) instead of being written to lpart / ediag.
+// jl0: first key column of the tile relative to the panel of width W that p.E holds.  STREAM: streaming stores
+// (written once, read by later kernels: keeps the operand tiles in L2).  STAGE: also leave the bf16 tile in LDS,
+// row-major 256 x 256 (8-byte granules XOR-swizzled with the row: conflict-free 8-byte writes and 16-byte reads),
+// for a caller that wants sums down its columns.
 constexpr int64_t NO_SELF = -((int64_t)1 << 40);
 
 enum { MASK_NONE = 0, MASK_DIAG = 1, MASK_EDGE = 2 };     // MASK_EDGE: label / left-out columns and padding columns
 
-template <bool STATS, bool STORE, int MASK, bool LOCAL = false>
+template <bool STATS, bool STORE, int MASK, bool LOCAL = false, bool STAGE = false, bool STREAM = true>
 __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)[4][2], char* smem, int64_t b, float s2, int64_t i0,
                                                int64_t j0, int64_t lab0, int64_t self0, int64_t nkeys, const float (&ref2)[2],
-                                               float* rs = nullptr, float* ed = nullptr) {
+                                               int64_t jl0, int64_t W, float* rs = nullptr, float* ed = nullptr) {
   constexpr bool DIAG = MASK != MASK_NONE, EDGE = MASK == MASK_EDGE;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 2, wn = wave & 3, half = lane >> 5;
@@ -248,9 +254,12 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
     const int jlim = jl64 >= 128 ? 128 : jl64 > 0 ? (int)jl64 : 0;
     float rowsum = 0.f;
     char* lrow = smem + il * E_ROW_BYTES;
+    // this lane's atom of the wave's first key piece pair: row i, key piece (jl0 + 128 wm) / 8 + half
+    uint16_t* erow = STORE ? p.E + ((i >> 6) * (W >> 3) + ((jl0 + wm * 128) >> 3) + half) * 512 + (i & 63) * 8 : nullptr;
 #pragma unroll
     for (int bm = 0; bm < 4; ++bm) {
       const int jl = wm * 128 + bm * 32 + half * 4;
+      u32x2 pk[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         float e[4];
@@ -269,13 +278,26 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
             if (dm == bm * 32 + q * 8 + r || (EDGE && bm * 32 + q * 8 + r >= jlim)) e[r] = 0.f;
         }
         if (STATS) rowsum += (e[0] + e[1]) + (e[2] + e[3]);
-        if (STORE) {
-          bf16x4 pk;
+        if (STORE || STAGE) {
+          bf16x4 v;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) pk[r] = (__bf16)e[r];
+          for (int r = 0; r < 4; ++r) v[r] = (__bf16)e[r];
+          pk[q] = __builtin_bit_cast(u32x2, v);
           // 8-byte granule g of row il lives at granule g ^ (il & 31): the 32 rows of a half-wave (same g)
           // then cover all 64 banks once
-          *reinterpret_cast<bf16x4*>(lrow + ((((jl >> 2) + q * 2) ^ (il & 31)) << 3)) = pk;
+          if (STAGE) *reinterpret_cast<u32x2*>(lrow + ((((jl >> 2) + q * 2) ^ (il & 31)) << 3)) = pk[q];
+        }
+      }
+      if (STORE) {
+#pragma unroll
+        for (int qp = 0; qp < 2; ++qp) {
+          // lanes 32..63 of the even piece's registers <-> lanes 0..31 of the odd piece's
+          const auto w0 = __builtin_amdgcn_permlane32_swap(pk[2 * qp][0], pk[2 * qp + 1][0], false, false);
+          const auto w1 = __builtin_amdgcn_permlane32_swap(pk[2 * qp][1], pk[2 * qp + 1][1], false, false);
+          const u32x4 atom = {w0[0], w1[0], w0[1], w1[1]};
+          u32x4* dst = reinterpret_cast<u32x4*>(erow + (bm * 4 + qp * 2) * 512);
+          if (STREAM) __builtin_nontemporal_store(atom, dst);
+          else *dst = atom;
         }
       }
     }
@@ -288,31 +310,11 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
   }
 }
 
-// Copies the staged 256 x 256 bf16 numerator tile (see logit_epilogue) from LDS to the blocked E panel of
-// width W; jl0 = first key column of the tile relative to the panel.  Barriers on both sides: every wave has
-// staged its part before the copy, and the staged tile has been read before the next tile loads into LDS.
-__device__ __forceinline__ void store_staged_numerators(const BlockPtrs& p, const char* smem, int64_t i0, int64_t jl0, int64_t W) {
-  lds_barrier();
-  const int t = threadIdx.x;
-  const int chunk16 = t & 31, r0 = t >> 5;   // 32 chunks of 16 bytes per 512-byte row; 16 rows per pass
-#pragma unroll 8
-  for (int r = 0; r < 16; ++r) {
-    const int row = r * 16 + r0;
-    // undo the granule swizzle: the 16-byte chunk moved as a whole, its halves swapped in odd rows
-    const u32x4 raw = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + ((chunk16 ^ ((row & 31) >> 1)) << 4));
-    const u32x4 val = (row & 1) ? u32x4{raw[2], raw[3], raw[0], raw[1]} : raw;
-    // written once, read by later kernels: streaming stores keep the operand tiles in L2
-    const int64_t i = i0 + row, jl = jl0 + chunk16 * 8;
-    __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(p.E + e_index(i, jl, W)));
-  }
-  lds_barrier();
-}
-
 // Logit tile + softmax numerators for the key panel [jp0, jp0 + W).  Tile rows (MFMA M side) are key rows
 // j, tile columns (N side) are query rows i, so that each lane holds 4 consecutive j of one query row per
 // accumulator quad: 8-byte pieces of an E row and an in-lane row sum.
 //   STATS: write the partial row sums and the label-column numerator (forward statistics);
-//   STORE: write the bf16 numerators to E (panel-relative columns, 64 x 64 blocked storage, see e_index).
+//   STORE: write the bf16 numerators to E (panel-relative columns, atom storage, see e_index).
 // materialized path: STATS and STORE, one panel = all keys.  fused path: a STATS-only pass over all
 // keys (nothing of size b x B is written), then STORE-only passes that recompute one panel at a time.
 // A STATS pass derives the rows' exponent references (row_reference; k_row_merge records the same values in ref2);
@@ -392,9 +394,8 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
     // Only the tiles that the label diagonal (or the left-out diagonal) crosses, or that hold padding columns, pay
     // for finding those columns.
     const bool diag = ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) || ((self0 + i0 < j0 + BM) && (j0 < self0 + i0 + BN));
-    if (diag || (RAGGED && j0 + BM > B)) logit_epilogue<STATS, STORE, RAGGED ? MASK_EDGE : MASK_DIAG>(p, acc, smem, b, s2, i0, j0, lab0, self0, B, ref2);
-    else logit_epilogue<STATS, STORE, MASK_NONE>(p, acc, smem, b, s2, i0, j0, lab0, self0, B, ref2);
-    if (STORE) store_staged_numerators(p, smem, i0, j0 - jp0, W);
+    if (diag || (RAGGED && j0 + BM > B)) logit_epilogue<STATS, STORE, RAGGED ? MASK_EDGE : MASK_DIAG>(p, acc, smem, b, s2, i0, j0, lab0, self0, B, ref2, j0 - jp0, W);
+    else logit_epilogue<STATS, STORE, MASK_NONE>(p, acc, smem, b, s2, i0, j0, lab0, self0, B, ref2, j0 - jp0, W);
   }
 }
 
@@ -538,9 +539,8 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
     mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
     const bool diag = ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) || ((self0 + i0 < j0 + BM) && (j0 < self0 + i0 + BN)) ||
                       j0 + BM > bl.keys;
-    if (diag) logit_epilogue<true, STORE, MASK_EDGE, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, bl.keys, ref2, rs, ed);
-    else logit_epilogue<true, STORE, MASK_NONE, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, bl.keys, ref2, rs, ed);
-    if (STORE) store_staged_numerators(p, smem, i0, j0, B);
+    if (diag) logit_epilogue<true, STORE, MASK_EDGE, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, bl.keys, ref2, j0, B, rs, ed);
+    else logit_epilogue<true, STORE, MASK_NONE, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, bl.keys, ref2, j0, B, rs, ed);
   }
   // row totals: the four lanes (two key halves x two lane halves) that share a row; exactly one of them met the label
   __syncthreads();
@@ -606,7 +606,7 @@ __global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   const int ncols = d - k0 < BN ? (int)(d - k0) : BN;              // the last column tile may be partial (d % 64 == 0)
-  mainloop<FMT_RB, FMT_K, true>(p.E + (jl0 >> 6) * 4096, (W >> 6) * 4096, p.Xs + k0 * b, b, (int)(b / BK), smem, acc, ncols);
+  mainloop<FMT_RA, FMT_K, true>(p.E + (jl0 >> 6) * 4096, (W >> 6) * 4096, p.Xs + k0 * b, b, (int)(b / BK), smem, acc, ncols);
   const int64_t left = bl.keys - (jp0 + jl0);                      // key rows that exist from this tile's first one on
   store_tile_f32<ACCUMULATE>(acc, smem, p.gk + (jp0 + jl0) * d + k0, d, cs, ncols, left < BM ? (int)left : BM);
 }
@@ -655,7 +655,7 @@ __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   const int ncols = d - k0 < BN ? (int)(d - k0) : BN;              // the last column tile may be partial (d % 64 == 0)
   if (kts > 0)
-    mainloop<FMT_KB, FMT_R, false>(p.E + ((i0 >> 6) * (W >> 6) + kt0) * 4096, (W >> 6) * 4096,
+    mainloop<FMT_KA, FMT_R, false>(p.E + ((i0 >> 6) * (W >> 6) + kt0) * 4096, (W >> 6) * 4096,
                                    p.Y + (jp0 + (int64_t)kt0 * BK) * d + k0, d, kts, smem, acc, ncols);
   store_tile_f32<ACCUMULATE>(acc, smem, p.part + (int64_t)ks * b * d + i0 * d + k0, d, 1.0f, ncols);
 }
@@ -805,9 +805,9 @@ __global__ __launch_bounds__(1024) void k_sym_ref(const float* zd2, int64_t B, c
 
 // Logit tiles of the symmetric path: k_logit_tiles for one block (X = I on the tile's N side, Y = T on its M side)
 // with the one reference; the row sums come from the accumulators as there, the column sums (over the tile's
-// query rows) from the staged bf16 tile while it is copied out: a thread adds up its 8 columns over its 16 rows,
-// lanes l and l + 32 join, the eight waves leave their sums in ring unit 4 and, after the barrier that ends the
-// copy, 256 threads add the eight.  (So the text -> image normalisation is that of the stored, rounded numerators.)
+// query rows) from a copy of the bf16 tile that the epilogue leaves in LDS: a thread adds up its 8 columns over its
+// 16 rows, lanes l and l + 32 join, the eight waves leave their sums in ring unit 4 and, after a barrier, 256
+// threads add the eight.  (So the text -> image normalisation is that of the stored, rounded numerators.)
 // bl.z[0]: E, row partial sums, label numerators; bl.z[1].lpart: column partial sums, one per query tile, cpart[it][j].
 __global__ __launch_bounds__(NTHREADS) void k_sym_logit(Blocks bl, int64_t B, int64_t d, float s2, const float* rglobal, int sbi, int sbj) {
   if (gated_off(bl)) return;
@@ -834,8 +834,9 @@ __global__ __launch_bounds__(NTHREADS) void k_sym_logit(Blocks bl, int64_t B, in
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
     // the label of query row i is key row i: only the tiles on the diagonal contain label columns
-    if (it == jt) logit_epilogue<true, true, MASK_DIAG>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, B, ref2);
-    else logit_epilogue<true, true, MASK_NONE>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, B, ref2);
+    // (ordinary stores: the matrix is read again by the combining pass and the two contractions)
+    if (it == jt) logit_epilogue<true, true, MASK_DIAG, false, true, false>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, B, ref2, j0, B);
+    else logit_epilogue<true, true, MASK_NONE, false, true, false>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, B, ref2, j0, B);
     lds_barrier();
     const int t = threadIdx.x;
     const int chunk16 = t & 31, r0 = t >> 5;
@@ -845,8 +846,6 @@ __global__ __launch_bounds__(NTHREADS) void k_sym_logit(Blocks bl, int64_t B, in
       const int row = r * 16 + r0;
       const u32x4 raw = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + ((chunk16 ^ ((row & 31) >> 1)) << 4));
       const u32x4 val = (row & 1) ? u32x4{raw[2], raw[3], raw[0], raw[1]} : raw;
-      // read again by the combining pass and the two contractions: ordinary stores
-      *reinterpret_cast<u32x4*>(p.E + e_index(i0 + row, j0 + chunk16 * 8, B)) = val;
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         cs[2 * w] += bf16_lo(val[w]);
@@ -871,7 +870,7 @@ __global__ __launch_bounds__(NTHREADS) void k_sym_logit(Blocks bl, int64_t B, in
 }
 
 // G_ij = E_ij (beta^A_i + beta^C_j) in place, bf16 (nearest even); the label entries stay 0.  A workgroup takes
-// 64 x 64 blocks of the blocked matrix one after the other; a thread 2 x 8 consecutive entries of a block.
+// 64 x 64 blocks of the matrix (8 KiB contiguous, see e_index) one after the other; a thread 2 atoms of a block.
 __global__ __launch_bounds__(256) void k_sym_combine(Blocks bl, int64_t B) {
   if (gated_off(bl)) return;
   const float* betaA = bl.z[0].beta;
@@ -883,9 +882,9 @@ __global__ __launch_bounds__(256) void k_sym_combine(Blocks bl, int64_t B) {
     const int64_t ib = blk / nb, jb = blk % nb;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int c = h * 256 + t;                          // 16-byte chunk of the block: row c >> 3, columns 8 (c & 7) ..
-      const int row = c >> 3, col = (c & 7) * 8;
-      u32x4* ptr = reinterpret_cast<u32x4*>(E + blk * 4096 + row * 64 + col);
+      const int c = h * 256 + t;                          // atom of the block: key piece c >> 6, row c & 63
+      const int row = c & 63, col = (c >> 6) * 8;
+      u32x4* ptr = reinterpret_cast<u32x4*>(E + blk * 4096 + c * 8);
       const u32x4 raw = *ptr;
       const float ba = betaA[ib * 64 + row];
       const f32x4 bc0 = *reinterpret_cast<const f32x4*>(betaC + jb * 64 + col);

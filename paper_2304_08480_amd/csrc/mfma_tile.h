@@ -29,11 +29,21 @@
 // A direct-to-LDS load puts lane l's 16 bytes at (wave-uniform LDS base) + 16*l, so a swizzle is applied by
 // choosing which global chunk each lane fetches.
 //
-// FMT_KB / FMT_RB are the same two LDS formats for an operand kept in memory as 64 x 64 blocks (each block
-// 8 KiB, row-major, 128-byte rows; blocks of one block row contiguous; `ld` = elements between block rows):
-// FMT_KB reduces along a block row (a K-step is one block per 64 tile rows), FMT_RB reduces down the block
-// rows (a K-step is one block row, four blocks wide).  A K-step's tile is then four contiguous 8 KiB runs in
-// memory instead of 256 pieces of 128 bytes (or 64 of 512) a row pitch apart, which DRAM serves better.
+// FMT_KA / FMT_RA read an operand kept in memory in "atoms": 16-byte pieces holding 8 consecutive columns of one
+// row, laid out by groups of 64 rows, inside a group column piece by column piece, inside a column piece row by
+// row: element (r, c) at ((r / 64) * (ncols / 8) + c / 8) * 512 + (r % 64) * 8 + c % 8; `ld` = elements between
+// row groups (64 * ncols).  A column piece of a row group is 1 KiB of memory, a 64 x 64 block 8 KiB, and a producer
+// whose lanes hold 8 consecutive columns of 32 or 64 consecutive rows stores whole 512-byte or 1 KiB runs straight
+// from registers.
+//   FMT_KA reduces along the columns (a K-step is 8 column pieces of each of the tile's four row groups: four
+//          contiguous 8 KiB runs, and a load instruction fetches one column piece of one row group, 1 KiB).  Its LDS
+//          tile keeps that order too: column piece c of the K-step at 4096 c, inside it tile row r at 16 r; the 16
+//          consecutive rows a quarter-wave reads with ds_read_b128 are 256 contiguous bytes, so no swizzle.
+//   FMT_RA reduces down the rows (a K-step is one row group; the tile's 256 rows are 32 column pieces of it: one
+//          contiguous 32 KiB run, and a load instruction fetches one column piece, 1 KiB).  Its LDS tile keeps that
+//          order: column piece c at 1024 c, inside it reduction row kap at 16 (kap ^ 4 (c % 4)), so that the
+//          4 reduction rows x 4 column pieces x 2 halves which a half-wave reads at once with ds_read_b64_tr_b16
+//          cover a 256-byte bank window exactly.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -55,8 +65,10 @@ constexpr int NUNITS = 5;
 constexpr int SMEM_BYTES = NUNITS * UNIT_BYTES;   // all 160 KiB of the CU's LDS
 constexpr int NLD = 8;                            // load instructions per loading wave and unit
 
-enum { FMT_K = 0, FMT_R = 1, FMT_KB = 2, FMT_RB = 3 };
-constexpr bool fmt_is_k(int f) { return f == FMT_K || f == FMT_KB; }
+enum { FMT_K = 0, FMT_R = 1, FMT_KA = 2, FMT_RA = 3 };
+// bytes between the LDS destinations of a wave's consecutive load instructions (FMT_KA: the wave loads the 8 column
+// pieces of its row group, which lie 4 KiB apart; else its instructions fill 8 KiB contiguously)
+constexpr int lds_step(int f) { return f == FMT_KA ? 4096 : 1024; }
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
@@ -90,11 +102,20 @@ __device__ __forceinline__ void wait_frags(Frags& f) {
                : "memory");
 }
 
+// A pointer that is the same in every lane, handed to the compiler as scalar registers: the loads below then take
+// the form scalar base + 32-bit lane offset, with no 64-bit vector address arithmetic and no vector registers for it.
+__device__ __forceinline__ const char* uniform_ptr(const void* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
+}
+
 // ---- per-lane addressing of one operand
 template <int FMT, int NFRAG>
 struct Operand {
   uint32_t ld_off[NLD];     // byte offset of this lane's global chunk for the wave's load instructions
-  uint32_t rd[4];           // FMT_K: rd[ks] base for sub-step ks; FMT_R: rd[i] base for fragment i
+  uint32_t rd[4];           // FMT_K/KA: rd[ks] base for sub-step ks; FMT_R: rd[i] base for fragment i; FMT_RA: rd[h]
+                            // base of the fragment's first (h = 0) and second (h = 1) transposing read
   uint32_t lds_q;           // LDS byte offset (inside the operand tile) of the wave's first load instruction
 
   // lw: index 0..3 of this wave among the four that load this operand; row0: first tile row of this
@@ -103,28 +124,43 @@ struct Operand {
   // stay in bounds (the caller does not use the output rows or columns they feed)
   __device__ __forceinline__ void init(int64_t ld, int lw, int lane, int row0, int nvalid = BM) {
     const int wave = lw;
-    lds_q = NLD * wave * 1024;
+    lds_q = FMT == FMT_KA ? wave * 1024 : NLD * wave * 1024;
 #pragma unroll
     for (int n = 0; n < NLD; ++n) {
       const int q = NLD * wave + n;               // which 1 KiB slice of the 32 KiB tile
-      if (fmt_is_k(FMT)) {
+      if (FMT == FMT_K) {
         const int rho = 8 * q + (lane >> 3), pc = lane & 7;
         const int ch = (pc ^ ((rho >> 1) & 7)) << 3;
         const int rsrc = rho < nvalid ? rho : nvalid - 1;
-        if (FMT == FMT_K) ld_off[n] = (uint32_t)(((int64_t)rsrc * ld + ch) * 2);
-        else ld_off[n] = (uint32_t)(((int64_t)(rsrc >> 6) * ld + (rsrc & 63) * 64 + ch) * 2);
+        ld_off[n] = (uint32_t)(((int64_t)rsrc * ld + ch) * 2);
+      } else if (FMT == FMT_KA) {                   // row group `wave`, column piece n of the K-step, row `lane` of the group
+        ld_off[n] = (uint32_t)(((int64_t)wave * ld + n * 512 + lane * 8) * 2);
+      } else if (FMT == FMT_RA) {
+        const int c = q;                            // this instruction's column piece; lane = position in it
+        ld_off[n] = (uint32_t)((c * 512 + (lane ^ ((c & 3) << 2)) * 8) * 2);
       } else {
         const int kap = 2 * q + (lane >> 5), pcw = lane & 31;
         const int c0 = (((pcw >> 1) ^ ((kap & 3) << 1)) << 1) | (pcw & 1);
         const int c = (c0 << 3) < nvalid ? c0 : (nvalid >> 3) - 1;
-        if (FMT == FMT_R) ld_off[n] = (uint32_t)(((int64_t)kap * ld + (c << 3)) * 2);
-        else ld_off[n] = (uint32_t)(((c >> 3) * 4096 + kap * 64 + ((c & 7) << 3)) * 2);
+        ld_off[n] = (uint32_t)(((int64_t)kap * ld + (c << 3)) * 2);
       }
     }
-    if (fmt_is_k(FMT)) {
+    if (FMT == FMT_K) {
       const int row = row0 + (lane & 31), g = (row >> 1) & 7, kc = lane >> 5;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) rd[ks] = (uint32_t)(row * 128 + (((ks * 2 + kc) ^ g) << 4));
+    } else if (FMT == FMT_KA) {
+      const int row = row0 + (lane & 31), kc = lane >> 5;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) rd[ks] = (uint32_t)((ks * 2 + kc) * 4096 + row * 16);
+    } else if (FMT == FMT_RA) {
+      const int grp = lane >> 4, L = lane & 15, piece = L & 3;     // piece: 8-byte quarter of a 16-row (32-byte) group
+      const int c = ((row0 + (grp & 1) * 16) >> 3) + (piece >> 1);   // + 4 per fragment: c % 4 unchanged
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int kap = (grp >> 1) * 8 + (L >> 2) + 4 * h;           // + 16 ks: bits 2..3 unchanged
+        rd[h] = (uint32_t)(c * 1024 + ((kap ^ ((c & 3) << 2)) << 4) + (piece & 1) * 8);
+      }
     } else {
       const int grp = lane >> 4, L = lane & 15;
       const int kap = (grp >> 1) * 8 + (L >> 2);  // + 16 ks + 4 h, multiples of 4: (kap & 3) unchanged
@@ -138,11 +174,12 @@ struct Operand {
   // issue this wave's loads of the K-step whose tile starts at `base` into the unit at `lds`
   __device__ __forceinline__ void load(const uint16_t* base, char* lds) const {
     char* l0 = lds + __builtin_amdgcn_readfirstlane(lds_q);
+    const char* ub = uniform_ptr(base);
 #pragma unroll
     for (int n = 0; n < NLD; ++n) {
-      const char* gp = reinterpret_cast<const char*>(base) + ld_off[n];
+      const char* gp = ub + ld_off[n];
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
-                                       (__attribute__((address_space(3))) void*)(l0 + n * 1024), 16, 0, 0);
+                                       (__attribute__((address_space(3))) void*)(l0 + n * lds_step(FMT)), 16, 0, 0);
     }
   }
 };
@@ -152,7 +189,9 @@ __device__ __forceinline__ u32x4 join(u32x2 lo, u32x2 hi) { return u32x4{lo[0], 
 // fragment i of sub-step KS from the operand tile at LDS byte address `tile`
 template <int FMT, int NFRAG, int KS, int I>
 __device__ __forceinline__ u32x4 read_frag(const Operand<FMT, NFRAG>& op, uint32_t tile) {
-  if (fmt_is_k(FMT)) return ds_read128<I * 4096>(tile + op.rd[KS]);
+  if (FMT == FMT_K) return ds_read128<I * 4096>(tile + op.rd[KS]);
+  if (FMT == FMT_KA) return ds_read128<I * 512>(tile + op.rd[KS]);
+  if (FMT == FMT_RA) return join(ds_read64_tr<KS * 256 + I * 4096>(tile + op.rd[0]), ds_read64_tr<KS * 256 + I * 4096>(tile + op.rd[1]));
   return join(ds_read64_tr<KS * 8192>(tile + op.rd[I]), ds_read64_tr<KS * 8192 + 2048>(tile + op.rd[I]));
 }
 template <int FA, int FB, int KS>
@@ -178,10 +217,11 @@ template <int FMT, int NFRAG>
 __device__ __forceinline__ void mfma_block_loads(const Frags& f, f32x16 (&acc)[4][2], const Operand<FMT, NFRAG>& op,
                                                  const uint16_t* base, char* lds) {
   char* l0 = lds + __builtin_amdgcn_readfirstlane(op.lds_q);
+  const char* ub = uniform_ptr(base);
 #define DISCO_LD(n)                                                                                                         \
   __builtin_amdgcn_global_load_lds(                                                                                         \
-      (const __attribute__((address_space(1))) void*)(reinterpret_cast<const char*>(base) + op.ld_off[n]),                  \
-      (__attribute__((address_space(3))) void*)(l0 + n * 1024), 16, 0, 0)
+      (const __attribute__((address_space(1))) void*)(ub + op.ld_off[n]),                                                   \
+      (__attribute__((address_space(3))) void*)(l0 + n * lds_step(FMT)), 16, 0, 0)
   mfma1(acc[0][0], f.a[0], f.b[0]); DISCO_LD(0);
   mfma1(acc[0][1], f.a[0], f.b[1]); DISCO_LD(1);
   mfma1(acc[1][0], f.a[1], f.b[0]); DISCO_LD(2);
@@ -210,12 +250,17 @@ __device__ __forceinline__ int ring_next(int u, int step) { u += step; return u 
 // So an A load has six sub-steps to land and a B load four.  Loads past the end are clamped to the last
 // K-step (redundant, never out of range, into a unit nobody reads again).
 // READS_FIRST: issue a sub-step's LDS reads ahead of its MFMAs (otherwise the compiler places them).
+template <int FMT>
+__device__ __forceinline__ int64_t kstep_elems(int64_t ld) {
+  return FMT == FMT_K ? BK : FMT == FMT_KA ? 4096 : FMT == FMT_R ? (int64_t)BK * ld : ld;
+}
+
 template <int FA, int FB, int GROUP, bool READS_FIRST>
 __device__ __forceinline__ void kloop(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ Bp, int64_t ldb,
                                       int ktiles, char* smem, f32x16 (&acc)[4][2], int nvalid_b) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int64_t stepA = FA == FMT_K ? BK : FA == FMT_KB ? 4096 : FA == FMT_R ? (int64_t)BK * lda : lda;
-  const int64_t stepB = FB == FMT_K ? BK : FB == FMT_KB ? 4096 : FB == FMT_R ? (int64_t)BK * ldb : ldb;
+  const int64_t stepA = kstep_elems<FA>(lda);
+  const int64_t stepB = kstep_elems<FB>(ldb);
   const int last = ktiles - 1;
   Operand<FA, 4> oa;
   Operand<FB, 2> ob;
@@ -279,7 +324,7 @@ __device__ __forceinline__ void kloop(const uint16_t* __restrict__ A, int64_t ld
 
 // acc[bm][bn] += A_tile(256 x K) * B_tile(256 x K)^T for this wave's 128 x 64 piece.
 //   FA / FB : tile format of the A / B operand (FMT_K: element (r,k) at base[r*ld + k]; FMT_R: at base[k*ld + r];
-//             FMT_KB / FMT_RB: the same for 64 x 64 blocked storage, see the top of this file).
+//             FMT_KA / FMT_RA: the same for storage in 16-byte atoms, see the top of this file).
 //   A, Bp   : element (row 0, k 0) of the workgroup's operand tiles; ktiles = K / 64 >= 1.
 //   smem    : SMEM_BYTES of LDS, 16-byte aligned; on return no load is in flight and every wave has passed
 //             a barrier, so the caller may reuse it at once.
