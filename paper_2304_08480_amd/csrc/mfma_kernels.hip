@@ -599,14 +599,8 @@ __global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int
   const int nt = lin % nN, mt = lin / nN;
   const int64_t jl0 = (int64_t)mt * BM, k0 = (int64_t)nt * BN;     // key rows jp0 + jl0 .. of the panel
   f32x16 acc[4][2];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   const int ncols = d - k0 < BN ? (int)(d - k0) : BN;              // the last column tile may be partial (d % 64 == 0)
-  mainloop<FMT_RA, FMT_K, true>(p.E + (jl0 >> 6) * 4096, (W >> 6) * 4096, p.Xs + k0 * b, b, (int)(b / BK), smem, acc, ncols);
+  mainloop<FMT_RA, FMT_K, true, true>(p.E + (jl0 >> 6) * 4096, (W >> 6) * 4096, p.Xs + k0 * b, b, (int)(b / BK), smem, acc, ncols);
   const int64_t left = bl.keys - (jp0 + jl0);                      // key rows that exist from this tile's first one on
   store_tile_f32<ACCUMULATE>(acc, smem, p.gk + (jp0 + jl0) * d + k0, d, cs, ncols, left < BM ? (int)left : BM);
 }
@@ -647,15 +641,9 @@ __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b
   int kts = kt_total - kt0;
   if (kts > ktiles_per_split) kts = ktiles_per_split;
   f32x16 acc[4][2];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   const int ncols = d - k0 < BN ? (int)(d - k0) : BN;              // the last column tile may be partial (d % 64 == 0)
-  if (kts > 0)
-    mainloop<FMT_KA, FMT_R, false>(p.E + ((i0 >> 6) * (W >> 6) + kt0) * 4096, (W >> 6) * 4096,
+  // (kts >= 1: the plan's split count is the number of splits that hold at least one K-step)
+  mainloop<FMT_KA, FMT_R, false, true>(p.E + ((i0 >> 6) * (W >> 6) + kt0) * 4096, (W >> 6) * 4096,
                                    p.Y + (jp0 + (int64_t)kt0 * BK) * d + k0, d, kts, smem, acc, ncols);
   store_tile_f32<ACCUMULATE>(acc, smem, p.part + (int64_t)ks * b * d + i0 * d + k0, d, 1.0f, ncols);
 }
