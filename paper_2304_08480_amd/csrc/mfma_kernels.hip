@@ -404,24 +404,58 @@ constexpr float ROW_TOTAL_FLOOR = 0x1p-60f;
 
 // beta, P_label - 1 and the cross-entropy of row i from its off-label sum, its label numerator and their total.
 // ce = log(tot / ed); when the label numerator does not dominate it is taken from the exponents,
-// log(tot) - (z2_label - ref2) ln 2, which stays finite when ed itself has underflowed.
-__device__ __forceinline__ void row_outputs(const BlockPtrs& p, int64_t i, float off, float ed, float tot) {
-  p.beta[i] = 1.f / tot;
+// log(tot) - (z2_label - ref2) ln 2, which stays finite when ed itself has underflowed.  Returns beta.
+__device__ __forceinline__ float row_outputs(const BlockPtrs& p, int64_t i, float off, float ed, float tot) {
+  const float beta = 1.f / tot;
+  p.beta[i] = beta;
   p.gdiag[i] = -off / tot;
   p.ce[i] = (ed > 0.5f * tot) ? log1pf(off / ed) : logf(tot) - (p.zd2[i] - p.ref2[i]) * LN2;
+  return beta;
+}
+
+// Xs[k][i] = bf16(scale_i x_ik) for the nrows (a multiple of 64) rows from i0 on, scale = the nrows floats at `scale`
+// in LDS (nullptr: 1): the key-side contraction's right operand, with its reduction index contiguous.  All threads of
+// the workgroup (a multiple of 256, at most 1024), 64 x 64 pieces through `tile` (64 x 65 floats of LDS).
+__device__ __forceinline__ void scale_transpose_rows(const BlockPtrs& p, int64_t b, int64_t d, int64_t i0, int nrows, const float* scale,
+                                                     float (*tile)[65]) {
+  const int t = threadIdx.x, nth = blockDim.x;
+  for (int r0 = 0; r0 < nrows; r0 += 64)
+    for (int64_t k0 = 0; k0 < d; k0 += 64) {
+      __syncthreads();                                    // the tile's previous contents have been read
+      for (int e = t; e < 1024; e += nth) {               // 64 rows x 16 pieces of 4 features
+        const int r = e >> 4, c4 = (e & 15) * 4;
+        const u32x2 w = *reinterpret_cast<const u32x2*>(p.X + (i0 + r0 + r) * d + k0 + c4);
+        const float sc = scale ? scale[r0 + r] : 1.f;
+        tile[r][c4 + 0] = sc * bf16_lo(w[0]);
+        tile[r][c4 + 1] = sc * bf16_hi(w[0]);
+        tile[r][c4 + 2] = sc * bf16_lo(w[1]);
+        tile[r][c4 + 3] = sc * bf16_hi(w[1]);
+      }
+      __syncthreads();
+      for (int e = t; e < 1024; e += nth) {               // 64 features x 16 pieces of 4 rows
+        const int k = e >> 4, i4 = (e & 15) * 4;
+        bf16x4 v;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (__bf16)tile[i4 + j][k];
+        *reinterpret_cast<bf16x4*>(p.Xs + (k0 + k) * b + i0 + r0 + i4) = v;
+      }
+    }
 }
 
 // Row totals -> beta, P_label - 1, cross-entropy.  A workgroup takes 64 rows; its 16 waves each add a
 // sixteenth of the column parts (lane = row, so the reads are coalesced), combined in fixed order.
 // nparts0 / nparts1: number of partial sums per row of block 0 / block 1.  global_ref (symmetric full loss): the one
 // exponent reference every row shares; bad_flag: where that path records that a row or column total was lost
-// (the per-rank paths flag the row's query tile for repair instead).
+// (the per-rank paths flag the row's query tile for repair instead).  d > 0: the workgroup goes on to write its
+// rows of Xs = (beta x)^T (a query tile that is repaired afterwards rewrites its rows there); d = 0: not.
 __global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int nparts0, int nparts1, float s2,
-                                                    const float* global_ref, int* bad_flag) {
+                                                    const float* global_ref, int* bad_flag, int64_t d) {
   if (gated_off(bl)) return;
   const int nparts = blockIdx.y ? nparts1 : nparts0;
   __shared__ float red[16][64];
   __shared__ float ymax_w[8];
+  __shared__ float beta_s[64];
+  __shared__ float tile[64][65];
   const BlockPtrs& p = bl.z[blockIdx.y];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   // max_j |y_j| folded from the partial maxima exactly as k_logit_tiles folds it (max is exact in any order)
@@ -444,27 +478,30 @@ __global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int np
   }
   red[wave][lane] = (a0 + a1) + (a2 + a3);
   __syncthreads();
-  if (wave != 0 || i >= b) return;
-  if (i >= bl.rows) {                                   // a padding row: no weight anywhere, no flag
-    p.ref2[i] = 0.f; p.beta[i] = 0.f; p.gdiag[i] = 0.f; p.ce[i] = 0.f;
-    return;
-  }
-  float off = 0.f;
+  if (wave == 0 && i < b) {
+    if (i >= bl.rows) {                                 // a padding row: no weight anywhere, no flag
+      p.ref2[i] = 0.f; p.beta[i] = 0.f; p.gdiag[i] = 0.f; p.ce[i] = 0.f;
+      beta_s[lane] = 0.f;
+    } else {
+      float off = 0.f;
 #pragma unroll
-  for (int w = 0; w < 16; w += 4) off += (red[w][lane] + red[w + 1][lane]) + (red[w + 2][lane] + red[w + 3][lane]);
-  float ym = ymax_w[0];
+      for (int w = 0; w < 16; w += 4) off += (red[w][lane] + red[w + 1][lane]) + (red[w + 2][lane] + red[w + 3][lane]);
+      float ym = ymax_w[0];
 #pragma unroll
-  for (int w = 1; w < 8; ++w) ym = fmaxf(ym, ymax_w[w]);
-  p.ref2[i] = global_ref ? *global_ref : row_reference(p.zd2[i], p.xnorm[i], sqrtf(ym), s2);   // what the statistics pass used
-  const float ed = p.ediag[i];
-  const float tot = off + ed;
-  row_outputs(p, i, off, ed, tot);
-  // The guard lifted the reference so far above every logit of this row that its total is (next to) lost:
-  // the row's query tile is redone against the true row maximum.  Also catches non-finite totals.
-  if (!(tot >= ROW_TOTAL_FLOOR)) {
-    if (bad_flag) *bad_flag = 1;
-    else p.tileflag[i >> 8] = 1;
+      for (int w = 1; w < 8; ++w) ym = fmaxf(ym, ymax_w[w]);
+      p.ref2[i] = global_ref ? *global_ref : row_reference(p.zd2[i], p.xnorm[i], sqrtf(ym), s2);   // what the statistics pass used
+      const float ed = p.ediag[i];
+      const float tot = off + ed;
+      beta_s[lane] = row_outputs(p, i, off, ed, tot);
+      // The guard lifted the reference so far above every logit of this row that its total is (next to) lost:
+      // the row's query tile is redone against the true row maximum.  Also catches non-finite totals.
+      if (!(tot >= ROW_TOTAL_FLOOR)) {
+        if (bad_flag) *bad_flag = 1;
+        else p.tileflag[i >> 8] = 1;
+      }
+    }
   }
+  if (d > 0 && (int64_t)blockIdx.x * 64 + 64 <= b) scale_transpose_rows(p, b, d, (int64_t)blockIdx.x * 64, 64, beta_s, tile);
 }
 
 // The statistics kernels of a flagged query tile, redone by one workgroup per (block, query tile): a first
@@ -560,10 +597,14 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
       const int il = wn * 64 + bn * 32 + lane;
       const float off = red[il] + red[256 + il], e = red[512 + il] + red[768 + il];
       p.ediag[i0 + il] = e;
-      if (i0 + il < bl.rows) row_outputs(p, i0 + il, off, e, off + e);
+      float beta = 0.f;
+      if (i0 + il < bl.rows) beta = row_outputs(p, i0 + il, off, e, off + e);
       else { p.beta[i0 + il] = 0.f; p.gdiag[i0 + il] = 0.f; p.ce[i0 + il] = 0.f; }
+      red[1024 + il] = beta;
     }
   }
+  // the rows' share of Xs = (beta x)^T, written by k_row_merge with the betas that have just been replaced
+  scale_transpose_rows(p, b, d, i0, BN, red + 1024, reinterpret_cast<float (*)[65]>(red + 1280));
 }
 
 // Xs[k][i] = bf16(beta_i * x_ik): the key-side contraction's right operand with the reduction index contiguous.
@@ -1108,10 +1149,9 @@ int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_
     else k_logit_tiles<true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, pl.B_real, d, g0, s2, 0, B, sbi, sbj, nblk);
   }
   if (marks) stage_mark(st, stage++);
-  k_row_merge<<<dim3((unsigned)((b + 63) / 64), (unsigned)nblk), 1024, 0, st>>>(bl, b, pl.nparts, pl.nparts, s2, nullptr, nullptr);
+  k_row_merge<<<dim3((unsigned)(b / 64), (unsigned)nblk), 1024, 0, st>>>(bl, b, pl.nparts, pl.nparts, s2, nullptr, nullptr, d);
   if (fused) k_logit_repair<false><<<dim3((unsigned)(nblk * nI)), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2);
   else k_logit_repair<true><<<dim3((unsigned)(nblk * nI)), NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, B, d, pr.rank, s2);
-  k_scale_transpose<<<dim3((unsigned)(b / 64), (unsigned)(d / 64), (unsigned)nblk), 256, 0, st>>>(bl, b, d, 1);
   if (marks) stage_mark(st, stage++);
 
   for (int pnl = 0; pnl < pl.npanels; ++pnl) {
@@ -1221,7 +1261,7 @@ int mfma_sym_run_impl(const Problem& pr) {
   stage_mark(st, stage++);
   Blocks both = bl;
   both.nblk = 2;
-  k_row_merge<<<dim3((unsigned)((B + 63) / 64), 2), 1024, 0, st>>>(both, B, pl.nparts, nT, s2, rglobal, gate);
+  k_row_merge<<<dim3((unsigned)((B + 63) / 64), 2), 1024, 0, st>>>(both, B, pl.nparts, nT, s2, rglobal, gate, 0);
   Blocks go = bl;                                   // from here on only while no total was lost
   go.gate = gate;
   go.gate_value = 0;
