@@ -33,7 +33,7 @@ using namespace tile;
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float REF_HEADROOM = 100.f;                    // largest exponent (base 2) a stored numerator may reach
 
-constexpr int E_ROW_BYTES = BM * 2;                      // row of the staged numerator tile (swizzled, not padded)
+constexpr int E_ROW_BYTES = BM * 2;                      // row of the bf16 tile copy in LDS (swizzled, not padded)
 constexpr int E_TILE_BYTES = BN * E_ROW_BYTES;            // 128 KiB
 constexpr int LOGIT_SMEM_BYTES = E_TILE_BYTES > SMEM_BYTES ? E_TILE_BYTES : SMEM_BYTES;
 constexpr int GEMM_SMEM_BYTES = OUT_SMEM_BYTES > SMEM_BYTES ? OUT_SMEM_BYTES : SMEM_BYTES;
@@ -607,23 +607,12 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
   scale_transpose_rows(p, b, d, i0, BN, red + 1024, reinterpret_cast<float (*)[65]>(red + 1280));
 }
 
-// Xs[k][i] = bf16(beta_i * x_ik): the key-side contraction's right operand with the reduction index contiguous.
-// scaled = 0: plain transpose (the symmetric full loss folds both normalisations into the stored matrix instead).
-__global__ __launch_bounds__(256) void k_scale_transpose(Blocks bl, int64_t b, int64_t d, int scaled) {
+// Xs = X^T for one block without any scaling (the symmetric full loss folds both normalisations into the stored
+// matrix instead): a workgroup per 64 rows.
+__global__ __launch_bounds__(1024) void k_transpose(Blocks bl, int64_t b, int64_t d) {
   if (gated_off(bl)) return;
   __shared__ float tile[64][65];
-  const BlockPtrs& p = bl.z[blockIdx.z];
-  const int64_t i0 = (int64_t)blockIdx.x * 64, k0 = (int64_t)blockIdx.y * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int r = ty; r < 64; r += 4) {
-    const int64_t i = i0 + r;
-    tile[r][tx] = (scaled ? p.beta[i] : 1.f) * __uint_as_float((uint32_t)p.X[i * d + k0 + tx] << 16);
-  }
-  __syncthreads();
-  for (int r = ty; r < 64; r += 4) {
-    __bf16 v = (__bf16)tile[tx][r];
-    p.Xs[(k0 + r) * b + i0 + tx] = *reinterpret_cast<uint16_t*>(&v);
-  }
+  scale_transpose_rows(bl.z[0], b, d, (int64_t)blockIdx.x * 64, 64, nullptr, tile);
 }
 
 // Key-side gradient without its label-column term: gk[j][k] (+)= cs * sum_i E[i][j] Xs[k][i].
@@ -1265,7 +1254,7 @@ int mfma_sym_run_impl(const Problem& pr) {
   Blocks go = bl;                                   // from here on only while no total was lost
   go.gate = gate;
   go.gate_value = 0;
-  k_scale_transpose<<<dim3((unsigned)(B / 64), (unsigned)(d / 64), 1), 256, 0, st>>>(go, B, d, 0);
+  k_transpose<<<dim3((unsigned)(B / 64)), 1024, 0, st>>>(go, B, d);
   stage_mark(st, stage++);
   k_sym_combine<<<dim3((unsigned)(8 * persistent_wgs)), 256, 0, st>>>(go, B);
   stage_mark(st, stage++);
@@ -1292,7 +1281,7 @@ bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype, int variant) {
   // two-view loss: a 256-row query tile must lie within one view, so that its labels are one offset away
   if (variant == LOSS_NTXENT && (B % 2 != 0 || (B / 2) % 256 != 0 || b % 256 != 0)) return false;
   // per-lane load offsets are 32-bit byte offsets inside one operand tile: 256 rows of pitch b (Xs) or four block
-  // rows of pitch 64 W (blocked numerators) must stay below 4 GiB
+  // rows of pitch 64 W (row groups of the stored numerators) must stay below 4 GiB
   if (B > ((int64_t)1 << 23) || b > ((int64_t)1 << 22)) return false;      // (rounding up to whole tiles stays within them)
   return d % 64 == 0;
 }

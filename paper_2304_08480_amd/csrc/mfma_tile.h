@@ -1,5 +1,5 @@
 // Device-side building blocks of the bf16 MFMA path: the 256x256x64 NT tile main loop, the operand
-// tile formats and the LDS-staged tile store.  Included by mfma_kernels.hip only.
+// tile formats and the tile store of the fp32 outputs (through LDS).  Included by mfma_kernels.hip only.
 //
 // Shape of the loop.  A workgroup of 8 waves (two per SIMD) owns a 256x256 output tile; each wave owns
 // 128x64 of it as 4x2 MFMA 32x32x16 bf16 blocks with fp32 accumulators.  The reduction runs in K-steps of
