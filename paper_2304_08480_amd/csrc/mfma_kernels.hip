@@ -630,7 +630,7 @@ __global__ __launch_bounds__(NTHREADS) void k_key_grad(Blocks bl, int64_t b, int
   const int64_t jl0 = (int64_t)mt * BM, k0 = (int64_t)nt * BN;     // key rows jp0 + jl0 .. of the panel
   f32x16 acc[4][2];
   const int ncols = d - k0 < BN ? (int)(d - k0) : BN;              // the last column tile may be partial (d % 64 == 0)
-  mainloop<FMT_RA, FMT_K, true, true>(p.E + (jl0 >> 6) * 4096, (W >> 6) * 4096, p.Xs + k0 * b, b, (int)(b / BK), smem, acc, ncols);
+  mainloop<FMT_RA, FMT_K, false, true>(p.E + (jl0 >> 6) * 4096, (W >> 6) * 4096, p.Xs + k0 * b, b, (int)(b / BK), smem, acc, ncols);
   const int64_t left = bl.keys - (jp0 + jl0);                      // key rows that exist from this tile's first one on
   store_tile_f32<ACCUMULATE>(acc, smem, p.gk + (jp0 + jl0) * d + k0, d, cs, ncols, left < BM ? (int)left : BM);
 }
