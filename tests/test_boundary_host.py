@@ -162,3 +162,15 @@ def test_mfma_paths_refuse_sizes_beyond_their_32_bit_tile_offsets():
     assert dl.disco_resolve_path(big, 512, big // 256, dl.DISCO_BF16, dl.DISCO_PATH_MATERIALIZED) == -dl.DISCO_ERR_UNSUPPORTED
     assert dl.disco_resolve_path(big, 512, big // 256, dl.DISCO_BF16, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
     assert dl.disco_resolve_path(1 << 23, 512, (1 << 23) // 256, dl.DISCO_BF16, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_MATERIALIZED
+
+
+def test_auto_sends_ragged_shares_to_the_tile_kernels_when_large_enough():
+    dt = dl.DISCO_BF16
+    assert dl.disco_resolve_path(32000, 512, 8, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_MATERIALIZED
+    assert dl.disco_resolve_path(1000, 256, 2, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_MATERIALIZED
+    assert dl.disco_resolve_path(1100, 64, 1, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_MATERIALIZED
+    assert dl.disco_resolve_path(264, 64, 33, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
+    assert dl.disco_resolve_path(32, 64, 4, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
+    assert dl.disco_resolve_path(1000, 100, 2, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE       # d % 64 != 0
+    assert dl.disco_resolve_path(1000, 256, 1, dt, dl.DISCO_PATH_SYMMETRIC) < 0
+    assert dl.disco_workspace_bytes(1000, 256, 2, dt, dl.DISCO_PATH_MATERIALIZED) > dl.disco_workspace_bytes(1024, 256, 2, dt, dl.DISCO_PATH_MATERIALIZED)
