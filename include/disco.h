@@ -85,10 +85,10 @@ typedef enum { DISCO_F32 = 0, DISCO_BF16 = 1 } disco_dtype;
  *                         its transpose); one matrix of numerators (B*B*2 bytes) against one exponent
  *                         reference, turned in place into the combined gradient matrix, then one contraction
  *                         per feature gradient: 6*B^2*d flop instead of 12.  Shape limits of MATERIALIZED
- *                         and B % 256 == 0.  Inputs whose rows' or columns' largest logits lie more than about
+ *                         (a batch that is not whole 256-row tiles is padded in the workspace as there).  Inputs whose rows' or columns' largest logits lie more than about
  *                         60 (base 2) under the largest positive-pair logit are handed over, inside the same
  *                         call, to the MATERIALIZED kernels, so the workspace is sized for those as well.
- * DISCO_PATH_AUTO         the fastest path that supports the arguments: SYMMETRIC (N = 1, B % 256 == 0) or
+ * DISCO_PATH_AUTO         the fastest path that supports the arguments: SYMMETRIC (N = 1) or
  *                         MATERIALIZED when their shape limits hold, else NAIVE.  Feature widths that are not
  *                         a multiple of 64, fp32 inputs, and ragged shares of blocks smaller than
  *                         b*B = 2^18 logits (launch-bound either way) therefore run on the vector ALUs, for

@@ -51,11 +51,13 @@ int resolve(int64_t B, int64_t d, int32_t N, int dtype, int path, int variant = 
   const bool tiles = mfma_supported(B, d, N, dtype, variant);          // the bf16 tile kernels can take it
   const bool whole = tiles && mfma_whole_tiles(B, N);                  // without padding the share to 256-row tiles
   switch (path) {
-    case DISCO_PATH_AUTO:
-      if (whole) return N == 1 && variant == LOSS_CLIP ? DISCO_PATH_SYMMETRIC : DISCO_PATH_MATERIALIZED;
+    case DISCO_PATH_AUTO: {
+      const int fast = N == 1 && variant == LOSS_CLIP ? DISCO_PATH_SYMMETRIC : DISCO_PATH_MATERIALIZED;
+      if (whole) return fast;
       // a ragged share is padded to whole tiles: worth it once the padded block is more than a few tiles of work
       // (below that the call is launch-bound on either path and the fp32 one has fewer launches)
-      return tiles && (B / N) * B >= RAGGED_MIN_BLOCK ? DISCO_PATH_MATERIALIZED : DISCO_PATH_NAIVE;
+      return tiles && (B / N) * B >= RAGGED_MIN_BLOCK ? fast : DISCO_PATH_NAIVE;
+    }
     case DISCO_PATH_NAIVE:
       return DISCO_PATH_NAIVE;
     case DISCO_PATH_MATERIALIZED:
@@ -63,7 +65,7 @@ int resolve(int64_t B, int64_t d, int32_t N, int dtype, int path, int variant = 
     case DISCO_PATH_FUSED:
       return whole ? DISCO_PATH_FUSED : -DISCO_ERR_UNSUPPORTED;
     case DISCO_PATH_SYMMETRIC:
-      return N == 1 && variant == LOSS_CLIP && whole ? DISCO_PATH_SYMMETRIC : -DISCO_ERR_UNSUPPORTED;
+      return N == 1 && variant == LOSS_CLIP && tiles ? DISCO_PATH_SYMMETRIC : -DISCO_ERR_UNSUPPORTED;
     default:
       return -DISCO_ERR_UNSUPPORTED;
   }

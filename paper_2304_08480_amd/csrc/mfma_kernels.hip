@@ -827,6 +827,10 @@ __global__ __launch_bounds__(1024) void k_sym_ref(const float* zd2, int64_t B, c
 // 16 rows, lanes l and l + 32 join, the eight waves leave their sums in ring unit 4 and, after a barrier, 256
 // threads add the eight.  (So the text -> image normalisation is that of the stored, rounded numerators.)
 // bl.z[0]: E, row partial sums, label numerators; bl.z[1].lpart: column partial sums, one per query tile, cpart[it][j].
+// B: the batch rounded up to whole tiles.  RAGGED: the batch is not whole tiles (X and Y are zero-padded copies): the
+// last key tiles leave their padding columns out (so every row sum is right) and the column sums leave the padding
+// rows out; what the padding rows hold in E meets zero feature rows in both contractions.
+template <bool RAGGED>
 __global__ __launch_bounds__(NTHREADS) void k_sym_logit(Blocks bl, int64_t B, int64_t d, float s2, const float* rglobal, int sbi, int sbj) {
   if (gated_off(bl)) return;
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -853,8 +857,9 @@ __global__ __launch_bounds__(NTHREADS) void k_sym_logit(Blocks bl, int64_t B, in
     mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
     // the label of query row i is key row i: only the tiles on the diagonal contain label columns
     // (ordinary stores: the matrix is read again by the combining pass and the two contractions)
-    if (it == jt) logit_epilogue<true, true, MASK_DIAG, false, true, false>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, B, ref2, j0, B);
-    else logit_epilogue<true, true, MASK_NONE, false, true, false>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, B, ref2, j0, B);
+    if (it == jt || (RAGGED && j0 + BM > bl.keys))
+      logit_epilogue<true, true, RAGGED ? MASK_EDGE : MASK_DIAG, false, true, false>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, bl.keys, ref2, j0, B);
+    else logit_epilogue<true, true, MASK_NONE, false, true, false>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, bl.keys, ref2, j0, B);
     lds_barrier();
     const int t = threadIdx.x;
     const int chunk16 = t & 31, r0 = t >> 5;
@@ -864,6 +869,7 @@ __global__ __launch_bounds__(NTHREADS) void k_sym_logit(Blocks bl, int64_t B, in
       const int row = r * 16 + r0;
       const u32x4 raw = *reinterpret_cast<const u32x4*>(smem + row * E_ROW_BYTES + ((chunk16 ^ ((row & 31) >> 1)) << 4));
       const u32x4 val = (row & 1) ? u32x4{raw[2], raw[3], raw[0], raw[1]} : raw;
+      if (RAGGED && i0 + row >= bl.rows) continue;
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         cs[2 * w] += bf16_lo(val[w]);
@@ -905,6 +911,7 @@ __global__ __launch_bounds__(256) void k_sym_combine(Blocks bl, int64_t B) {
       u32x4* ptr = reinterpret_cast<u32x4*>(E + blk * 4096 + c * 8);
       const u32x4 raw = *ptr;
       const float ba = betaA[ib * 64 + row];
+      const bool padding = ib * 64 + row >= bl.rows;      // a padding row of a ragged batch: exact zeros, whatever it holds
       const f32x4 bc0 = *reinterpret_cast<const f32x4*>(betaC + jb * 64 + col);
       const f32x4 bc1 = *reinterpret_cast<const f32x4*>(betaC + jb * 64 + col + 4);
       const float bc[8] = {bc0[0], bc0[1], bc0[2], bc0[3], bc1[0], bc1[1], bc1[2], bc1[3]};
@@ -913,7 +920,7 @@ __global__ __launch_bounds__(256) void k_sym_combine(Blocks bl, int64_t B) {
       for (int w = 0; w < 4; ++w) {
         const __bf16 lo = (__bf16)(bf16_lo(raw[w]) * (ba + bc[2 * w]));
         const __bf16 hi = (__bf16)(bf16_hi(raw[w]) * (ba + bc[2 * w + 1]));
-        out[w] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+        out[w] = padding ? 0u : (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
       }
       *ptr = out;
     }
@@ -924,7 +931,8 @@ __global__ __launch_bounds__(256) void k_sym_combine(Blocks bl, int64_t B) {
 // without the label entry and gd = (P^A_ii - 1) + (P^C_ii - 1),
 //   gI[i] (+)= cs (u + gd T[i])      gT[i] += cs gd I[i]   (the key-side contraction has written or added its part)
 // and the row's share of d/ds, <u + gd T[i], I[i]> (sum_ij G_ij S_ij = <G T, I> with the label entries included).
-__global__ __launch_bounds__(256) void k_sym_finalize(Blocks bl, int64_t B, int64_t d, float cs, int splitk, int accumulate) {
+// B: the rows that exist; Bp: row pitch of the partial products.
+__global__ __launch_bounds__(256) void k_sym_finalize(Blocks bl, int64_t B, int64_t Bp, int64_t d, float cs, int splitk, int accumulate) {
   if (gated_off(bl)) return;
   const BlockPtrs& p = bl.z[0];
   const int lane = threadIdx.x & 63;
@@ -934,7 +942,7 @@ __global__ __launch_bounds__(256) void k_sym_finalize(Blocks bl, int64_t B, int6
   float dot = 0.f;
   for (int64_t k = lane * 4; k < d; k += 256) {
     f32x4 u = {0.f, 0.f, 0.f, 0.f};
-    for (int ks = 0; ks < splitk; ++ks) u += *reinterpret_cast<const f32x4*>(p.part + ((int64_t)ks * B + i) * d + k);
+    for (int ks = 0; ks < splitk; ++ks) u += *reinterpret_cast<const f32x4*>(p.part + ((int64_t)ks * Bp + i) * d + k);
     const u32x2 iw = *reinterpret_cast<const u32x2*>(p.X + i * d + k);
     const u32x2 tw = *reinterpret_cast<const u32x2*>(p.Y + i * d + k);
     const float iv[4] = {bf16_lo(iw[0]), bf16_hi(iw[0]), bf16_lo(iw[1]), bf16_hi(iw[1])};
@@ -1175,31 +1183,35 @@ size_t sym_tail(int64_t B, int64_t d) {
 }
 
 int mfma_sym_run_impl(const Problem& pr) {
-  static const bool lds_ok = allow_lds(k_sym_logit, LOGIT_SMEM_BYTES);
+  static const bool lds_ok = allow_lds(k_sym_logit<false>, LOGIT_SMEM_BYTES) && allow_lds(k_sym_logit<true>, LOGIT_SMEM_BYTES);
   if (!lds_ok) return DISCO_ERR_HIP;
   const Plan pl = make_plan(pr.B, pr.d, 1, false, 1);
   const int persistent_wgs = compute_units();
-  const int64_t B = pl.B, d = pl.d;
+  const int64_t B = pl.B, d = pl.d, Br = pl.B_real;        // whole tiles / the rows that exist
   char* ws = static_cast<char*>(pr.ws);
-  const size_t tail = sym_tail(B, d);
+  const size_t tail = sym_tail(Br, d);
   int* gate = reinterpret_cast<int*>(ws + tail);
   float* rglobal = reinterpret_cast<float*>(ws + tail + 128);
   const uint16_t* I = static_cast<const uint16_t*>(pr.I);
   const uint16_t* T = static_cast<const uint16_t*>(pr.T);
   float* wgmax = reinterpret_cast<float*>(ws + pl.off_ymax);
 
+  // a batch that is not whole tiles: zero-padded copies of I and T (the copies of "the rank's rows" are not used)
+  uint16_t* Ipad = reinterpret_cast<uint16_t*>(ws + pl.off_pad);
+  uint16_t* Tpad = reinterpret_cast<uint16_t*>(ws + pl.off_pad + align_up((size_t)B * d * 2));
+
   Blocks bl;
   bl.variant = LOSS_CLIP;
   bl.nblk = 1;
-  bl.rows = B;
-  bl.keys = B;
+  bl.rows = Br;
+  bl.keys = Br;
   bl.gate = nullptr;
   bl.gate_value = 0;
   BlockPtrs& p = bl.z[0];
   char* rows0 = ws + pl.off_rows;
   char* rows1 = rows0 + (size_t)NROWARRAYS * pl.rows_stride;
-  p.X = I;
-  p.Y = T;
+  p.X = pl.ragged ? Ipad : I;
+  p.Y = pl.ragged ? Tpad : T;
   p.E = reinterpret_cast<uint16_t*>(ws + pl.off_E);
   p.lpart = reinterpret_cast<float*>(ws + pl.off_lpart);
   p.ediag = reinterpret_cast<float*>(rows0 + 0 * pl.rows_stride);
@@ -1229,7 +1241,7 @@ int mfma_sym_run_impl(const Problem& pr) {
   q.tileflag = reinterpret_cast<int*>(ws + pl.off_flags + align_up((size_t)(B / BN) * 4));
 
   const float s2 = pr.s * LOG2E;
-  const float c = loss_norm(B, LOSS_CLIP);
+  const float c = loss_norm(Br, LOSS_CLIP);
   const float cs = c * pr.s;
   hipStream_t st = pr.stream;
   const int nT = (int)(B / BN);
@@ -1243,10 +1255,12 @@ int mfma_sym_run_impl(const Problem& pr) {
   int stage = 0;
 
   stage_mark(st, stage++);
-  k_prep<<<dim3((unsigned)(2 * NORM_BLOCKS + (B + 3) / 4)), 256, 0, st>>>(bl, I, T, B, B, B, d, 0, s2, wgmax);
-  k_sym_ref<<<1, 1024, 0, st>>>(p.zd2, B, wgmax, s2, rglobal, gate);
+  if (pl.ragged) k_pad_operands<<<dim3((unsigned)(8 * persistent_wgs)), 256, 0, st>>>(I, T, Br, B, 0, 0, d, 0, Ipad, Tpad, Ipad, Tpad);
+  k_prep<<<dim3((unsigned)(2 * NORM_BLOCKS + (B + 3) / 4)), 256, 0, st>>>(bl, I, T, Br, Br, B, d, 0, s2, wgmax);
+  k_sym_ref<<<1, 1024, 0, st>>>(p.zd2, Br, wgmax, s2, rglobal, gate);
   stage_mark(st, stage++);
-  k_sym_logit<<<logit_grid, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, B, d, s2, rglobal, sbi, sbj);
+  if (pl.ragged) k_sym_logit<true><<<logit_grid, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, B, d, s2, rglobal, sbi, sbj);
+  else k_sym_logit<false><<<logit_grid, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, B, d, s2, rglobal, sbi, sbj);
   stage_mark(st, stage++);
   Blocks both = bl;
   both.nblk = 2;
@@ -1263,10 +1277,10 @@ int mfma_sym_run_impl(const Problem& pr) {
   stage_mark(st, stage++);
   k_query_partial<false><<<dim3((unsigned)q_wgs), NTHREADS, GEMM_SMEM_BYTES, st>>>(go, B, d, 0, B, pl.nMq, pl.nN, pl.splitk, pl.ktps);
   stage_mark(st, stage++);
-  k_sym_finalize<<<dim3((unsigned)((B + 3) / 4)), 256, 0, st>>>(go, B, d, cs, pl.splitk, pr.accumulate);
+  k_sym_finalize<<<dim3((unsigned)((Br + 3) / 4)), 256, 0, st>>>(go, Br, B, d, cs, pl.splitk, pr.accumulate);
   Blocks go2 = go;
   go2.nblk = 2;
-  k_scalars<<<1, 1024, 0, st>>>(go2, B, c, pr.accumulate, pr.loss, pr.gs);
+  k_scalars<<<1, 1024, 0, st>>>(go2, Br, c, pr.accumulate, pr.loss, pr.gs);
   stage_mark(st, stage++);
   if (hipGetLastError() != hipSuccess) return DISCO_ERR_HIP;
   return mfma_run(pr, false, gate, 1, false);

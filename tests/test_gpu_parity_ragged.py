@@ -76,6 +76,33 @@ def test_ragged_share_matches_oracle(B, d, N, s):
     assert run.guards_intact()
 
 
+@pytest.mark.parametrize("B,d,s,kind", [(1100, 128, 25.0, None), (1100, 64, 14.285714, None), (1000, 256, 14.285714, None), (2310, 192, 14.285714, None),
+                                        (1400, 512, 100.0, "anti"), (1400, 512, 14.285714, "norms")])
+def test_ragged_batch_on_the_symmetric_path(B, d, s, kind):
+    """The non-decomposed loss of a batch that is not whole tiles, on the path that keeps one B x B matrix (AUTO takes
+    it): padding rows and columns stay out of both directions' sums; inputs that make it hand over to the two-block
+    kernels (anti-correlated positives at s = 100) go through the padding of both."""
+    I, T, Ib, Tb = _inputs(B, d, 25, kind=kind)
+    Id, Td, dt = to_device(I, T, Ib, Tb, "bf16")
+    assert dl.disco_resolve_path(B, d, 1, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_SYMMETRIC
+    zmax = abs(s) * float(np.linalg.norm(I, axis=1).max() * np.linalg.norm(T, axis=1).max())
+    run = GuardedRunner(Id, Td, B, d, 1, dt, dl.DISCO_PATH_AUTO)
+    print(f"case ragged symmetric B={B} d={d} s={s} {kind}", flush=True)
+    run.full(s)
+    ref = oc.clip_loss_full(I, T, s)
+    sc = term_scale(oc, I, T, s, 0, 1)
+    gsc = oc.disco_rank_gs_term_scale(I, T, s, 0, 1)
+    _compare(run, ref, sc, f"ragged symmetric B{B} d{d} s{s:g} {kind}", kind is not None, gsc, zmax if kind else 0.0)
+    assert run.guards_intact()
+    l0, a0, t0, g0 = run.results()
+    run.rank(0, s, accumulate=True)
+    l1, a1, t1, g1 = run.results()
+    assert l1 == pytest.approx(2 * l0, rel=1e-6) and g1 == pytest.approx(2 * g0, rel=1e-5, abs=1e-12)
+    np.testing.assert_allclose(a1, 2 * a0, rtol=1e-5, atol=2e-6 * np.abs(a0).max())
+    np.testing.assert_allclose(t1, 2 * t0, rtol=1e-5, atol=2e-6 * np.abs(t0).max())
+    assert run.guards_intact()
+
+
 @pytest.mark.parametrize("kind,s", [("big_norm_low_cos", 14.285714), ("anti", 100.0), ("zero_rows", 14.285714), ("duplicates", 100.0)])
 def test_ragged_share_on_inputs_that_are_not_clip_like(kind, s):
     """The exponent reference, its repair (big_norm_low_cos loses every row total in the first pass) and the padding
