@@ -58,6 +58,8 @@ def _compare(run, ref, scale, tag, cancelling=False, gs_scale=0.0, zmax=0.0):
     (2310, 192, 3, 14.285714),      # 770-row shares: the label diagonal of ranks 1 and 2 crosses tile corners
     (264, 64, 33, 14.285714),       # 8-row shares: a single mostly empty query tile
     (1800, 512, 8, 100.0),          # 225-row shares at the clamp of the logit multiplier
+    (512, 64, 512, 14.285714),      # one pair per rank
+    (1, 64, 1, 14.285714),          # a batch of one pair: loss 0, no gradient
 ])
 def test_ragged_share_matches_oracle(B, d, N, s):
     I, T, Ib, Tb = _inputs(B, d, 21)
@@ -76,17 +78,18 @@ def test_ragged_share_matches_oracle(B, d, N, s):
     assert run.guards_intact()
 
 
-@pytest.mark.parametrize("B,d,s,kind", [(1100, 128, 25.0, None), (1100, 64, 14.285714, None), (1000, 256, 14.285714, None), (2310, 192, 14.285714, None),
+@pytest.mark.parametrize("B,d,s,kind", [(64, 64, 14.285714, None), (1, 64, 14.285714, None), (1100, 128, 25.0, None), (1100, 64, 14.285714, None), (1000, 256, 14.285714, None), (2310, 192, 14.285714, None),
                                         (1400, 512, 100.0, "anti"), (1400, 512, 14.285714, "norms")])
 def test_ragged_batch_on_the_symmetric_path(B, d, s, kind):
     """The non-decomposed loss of a batch that is not whole tiles, on the path that keeps one B x B matrix (AUTO takes
     it): padding rows and columns stay out of both directions' sums; inputs that make it hand over to the two-block
-    kernels (anti-correlated positives at s = 100) go through the padding of both."""
+    kernels (anti-correlated positives at s = 100) go through the padding of both.  (AUTO takes this path for ragged
+    batches from 512 pairs on; the smaller ones here ask for it.)"""
     I, T, Ib, Tb = _inputs(B, d, 25, kind=kind)
     Id, Td, dt = to_device(I, T, Ib, Tb, "bf16")
-    assert dl.disco_resolve_path(B, d, 1, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_SYMMETRIC
+    assert dl.disco_resolve_path(B, d, 1, dt, dl.DISCO_PATH_SYMMETRIC) == dl.DISCO_PATH_SYMMETRIC
     zmax = abs(s) * float(np.linalg.norm(I, axis=1).max() * np.linalg.norm(T, axis=1).max())
-    run = GuardedRunner(Id, Td, B, d, 1, dt, dl.DISCO_PATH_AUTO)
+    run = GuardedRunner(Id, Td, B, d, 1, dt, dl.DISCO_PATH_SYMMETRIC)
     print(f"case ragged symmetric B={B} d={d} s={s} {kind}", flush=True)
     run.full(s)
     ref = oc.clip_loss_full(I, T, s)
