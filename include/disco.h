@@ -79,7 +79,7 @@ typedef enum { DISCO_F32 = 0, DISCO_BF16 = 1 } disco_dtype;
  *                         writes nothing of size b x B; the backward pass recomputes the logits one
  *                         key panel (at most 16384 keys) at a time and contracts each panel while
  *                         it is cache-resident (16*b*B*d flop, workspace 2*b*W*2 bytes for panel
- *                         width W).  Shape limits of MATERIALIZED and b % 256 == 0.
+ *                         width W).  Shape limits of MATERIALIZED (ragged shares padded as there).
  * DISCO_PATH_SYMMETRIC    bf16 MFMA tiles, N = 1 only (the non-decomposed loss, Eq. 1 / Fig. 1): the B x B
  *                         similarity matrix is computed once and serves both directions (text -> image is
  *                         its transpose); one matrix of numerators (B*B*2 bytes) against one exponent

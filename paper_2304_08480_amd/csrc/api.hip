@@ -63,7 +63,7 @@ int resolve(int64_t B, int64_t d, int32_t N, int dtype, int path, int variant = 
     case DISCO_PATH_MATERIALIZED:
       return tiles ? DISCO_PATH_MATERIALIZED : -DISCO_ERR_UNSUPPORTED;
     case DISCO_PATH_FUSED:
-      return whole ? DISCO_PATH_FUSED : -DISCO_ERR_UNSUPPORTED;
+      return tiles ? DISCO_PATH_FUSED : -DISCO_ERR_UNSUPPORTED;
     case DISCO_PATH_SYMMETRIC:
       return N == 1 && variant == LOSS_CLIP && tiles ? DISCO_PATH_SYMMETRIC : -DISCO_ERR_UNSUPPORTED;
     default:

@@ -1057,6 +1057,7 @@ int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_
   // the tile kernels use more LDS than the default limit; raised once per process (one device per process here)
   static const bool lds_ok = allow_lds(k_logit_tiles<true, true>, LOGIT_SMEM_BYTES) && allow_lds(k_logit_tiles<true, false>, LOGIT_SMEM_BYTES) &&
                              allow_lds(k_logit_tiles<false, true>, LOGIT_SMEM_BYTES) && allow_lds(k_logit_tiles<true, true, true>, LOGIT_SMEM_BYTES) &&
+                             allow_lds(k_logit_tiles<true, false, true>, LOGIT_SMEM_BYTES) && allow_lds(k_logit_tiles<false, true, true>, LOGIT_SMEM_BYTES) &&
                              allow_lds(k_logit_repair<false>, LOGIT_SMEM_BYTES) &&
                              allow_lds(k_logit_repair<true>, LOGIT_SMEM_BYTES) && allow_lds(k_key_grad<false>, GEMM_SMEM_BYTES) &&
                              allow_lds(k_key_grad<true>, GEMM_SMEM_BYTES) && allow_lds(k_query_partial<false>, GEMM_SMEM_BYTES) &&
@@ -1064,7 +1065,7 @@ int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_
   if (!lds_ok) return DISCO_ERR_HIP;
   const int nblk = loss_blocks(pr.variant);
   const Plan pl = make_plan(pr.B, pr.d, pr.N, fused, nblk);
-  if (pl.ragged && (fused || pr.variant != LOSS_CLIP)) return DISCO_ERR_UNSUPPORTED;   // (the dispatch does not send these here)
+  if (pl.ragged && pr.variant != LOSS_CLIP) return DISCO_ERR_UNSUPPORTED;   // (the dispatch does not send these here)
   const int persistent_wgs = compute_units();
   const int64_t b = pl.b, B = pl.B, d = pl.d, W = pl.W;     // whole tiles; the real sizes are pl.b_real, pl.B_real
   char* ws = static_cast<char*>(pr.ws);
@@ -1139,7 +1140,8 @@ int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_
   int sbj;
   if (fused) {
     const dim3 g = logit_grid(B, sbj);
-    k_logit_tiles<true, false><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, pl.B_real, d, g0, s2, 0, B, sbi, sbj, nblk);
+    if (pl.ragged) k_logit_tiles<true, false, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, pl.B_real, d, g0, s2, 0, B, sbi, sbj, nblk);
+    else k_logit_tiles<true, false><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, pl.B_real, d, g0, s2, 0, B, sbi, sbj, nblk);
   } else {
     const dim3 g = logit_grid(B, sbj);
     if (pl.ragged) k_logit_tiles<true, true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, pl.B_real, d, g0, s2, 0, B, sbi, sbj, nblk);
@@ -1155,7 +1157,8 @@ int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_
     const int64_t jp0 = (int64_t)pnl * W;
     if (fused) {
       const dim3 g = logit_grid(W, sbj);
-      k_logit_tiles<false, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, pl.B_real, d, g0, s2, jp0, W, sbi, sbj, nblk);
+      if (pl.ragged) k_logit_tiles<false, true, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, pl.B_real, d, g0, s2, jp0, W, sbi, sbj, nblk);
+      else k_logit_tiles<false, true><<<g, NTHREADS, LOGIT_SMEM_BYTES, st>>>(bl, b, pl.B_real, d, g0, s2, jp0, W, sbi, sbj, nblk);
     }
     if (pr.accumulate)
       k_key_grad<true><<<key_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, cs, jp0, W, nMk, pl.nN);

@@ -173,5 +173,6 @@ def test_auto_sends_ragged_shares_to_the_tile_kernels_when_large_enough():
     assert dl.disco_resolve_path(32, 64, 4, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
     assert dl.disco_resolve_path(1000, 100, 2, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE       # d % 64 != 0
     assert dl.disco_resolve_path(1000, 256, 1, dt, dl.DISCO_PATH_SYMMETRIC) == dl.DISCO_PATH_SYMMETRIC
-    assert dl.disco_resolve_path(1000, 256, 1, dt, dl.DISCO_PATH_FUSED) < 0
+    assert dl.disco_resolve_path(1000, 256, 2, dt, dl.DISCO_PATH_FUSED) == dl.DISCO_PATH_FUSED
+    assert dl.ntxent_resolve_path(1000, 256, 2, dt, dl.DISCO_PATH_FUSED) < 0          # the two-view loss: whole tiles only
     assert dl.disco_workspace_bytes(1000, 256, 2, dt, dl.DISCO_PATH_MATERIALIZED) > dl.disco_workspace_bytes(1024, 256, 2, dt, dl.DISCO_PATH_MATERIALIZED)

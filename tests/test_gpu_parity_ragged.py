@@ -61,12 +61,12 @@ def _compare(run, ref, scale, tag, cancelling=False, gs_scale=0.0, zmax=0.0):
     (512, 64, 512, 14.285714),      # one pair per rank
     (1, 64, 1, 14.285714),          # a batch of one pair: loss 0, no gradient
 ])
-def test_ragged_share_matches_oracle(B, d, N, s):
+@pytest.mark.parametrize("path", [dl.DISCO_PATH_MATERIALIZED, dl.DISCO_PATH_FUSED], ids=["materialized", "fused"])
+def test_ragged_share_matches_oracle(B, d, N, s, path):
     I, T, Ib, Tb = _inputs(B, d, 21)
     Id, Td, dt = to_device(I, T, Ib, Tb, "bf16")
-    assert dl.disco_resolve_path(B, d, N, dt, dl.DISCO_PATH_MATERIALIZED) == dl.DISCO_PATH_MATERIALIZED
-    assert dl.disco_resolve_path(B, d, N, dt, dl.DISCO_PATH_FUSED) < 0          # whole tiles only
-    run = GuardedRunner(Id, Td, B, d, N, dt, dl.DISCO_PATH_MATERIALIZED)
+    assert dl.disco_resolve_path(B, d, N, dt, path) == path
+    run = GuardedRunner(Id, Td, B, d, N, dt, path)
     for r in sorted({0, N // 2, N - 1}):
         print(f"case ragged B={B} d={d} N={N} s={s} rank={r}", flush=True)
         run.rank(r, s)
@@ -114,13 +114,14 @@ def test_ragged_share_on_inputs_that_are_not_clip_like(kind, s):
     I, T, Ib, Tb = _inputs(B, d, 23, kind=kind)
     Id, Td, dt = to_device(I, T, Ib, Tb, "bf16")
     zmax = abs(s) * float(np.linalg.norm(I, axis=1).max() * np.linalg.norm(T, axis=1).max())
-    run = GuardedRunner(Id, Td, B, d, N, dt, dl.DISCO_PATH_MATERIALIZED)
-    for r in range(N):
-        print(f"case ragged {kind} s={s} rank={r}", flush=True)
-        run.rank(r, s)
-        _compare(run, oc.disco_rank(I, T, s, r, N), term_scale(oc, I, T, s, r, N), f"ragged {kind} s{s:g} rank {r}", True,
-                 oc.disco_rank_gs_term_scale(I, T, s, r, N), zmax)
-        assert run.guards_intact()
+    for path in (dl.DISCO_PATH_MATERIALIZED, dl.DISCO_PATH_FUSED):
+        run = GuardedRunner(Id, Td, B, d, N, dt, path)
+        for r in range(N):
+            print(f"case ragged {kind} s={s} rank={r} path={path}", flush=True)
+            run.rank(r, s)
+            _compare(run, oc.disco_rank(I, T, s, r, N), term_scale(oc, I, T, s, r, N), f"ragged {kind} s{s:g} rank {r} path {path}", True,
+                     oc.disco_rank_gs_term_scale(I, T, s, r, N), zmax)
+            assert run.guards_intact()
 
 
 def test_ragged_share_agrees_with_the_padded_problem_rows():
