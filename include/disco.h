@@ -151,8 +151,8 @@ DISCO_API int clip_loss_fwd_bwd(const void* I, const void* T, int64_t B, int64_t
  * that the SUM over ranks is the full result: loss_r, gs_r = d loss_r / d s, and gZ_r (B x d fp32): the query-side
  * gradient in the rank's own rows plus the key-side gradient in all B rows (the part Eq. 5 / Eq. 7 would send to
  * the other ranks).  Arguments, ownership, errors, paths, `accumulate`, stream and capture rules are those of
- * disco_loss_fwd_bwd, with one matrix Z for I and T and one gradient gZ; B odd is DISCO_ERR_SHAPE; the bf16 MFMA
- * paths additionally need (B/2) % 256 == 0 and b % 256 == 0.  ntxent_workspace_bytes / ntxent_resolve_path are this entry's
+ * disco_loss_fwd_bwd, with one matrix Z for I and T and one gradient gZ; B odd is DISCO_ERR_SHAPE; there is no
+ * symmetric path for this loss.  ntxent_workspace_bytes / ntxent_resolve_path are this entry's
  * counterparts of disco_workspace_bytes / disco_resolve_path.
  */
 DISCO_API int ntxent_resolve_path(int64_t B, int64_t d, int32_t N, int dtype, int path);

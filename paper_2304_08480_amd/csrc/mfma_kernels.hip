@@ -221,8 +221,9 @@ __global__ __launch_bounds__(256) void k_pad_operands(const uint16_t* I, const u
 // consecutive query rows) then store 512 contiguous bytes of the panel (see e_index): no LDS, no barrier, so
 // the waves of a workgroup need not meet between the main loops of consecutive tiles.
 // MASK_DIAG: the tile contains label columns, which are stored as 0 and kept in fp32 in ediag.
-// The label of query row i is key row lab0 + i; key row self0 + i is left out of row i's softmax (stored as 0, in
-// no sum; self0 far negative: no such column), and so are the padding columns from key row nkeys on (MASK_EDGE only:
+// Local query row i is global row g0 + i; its label is key row label_row(g0 + i), and for the two-view loss its own
+// key row g0 + i is left out of its softmax (stored as 0, in no sum), and so are the padding columns from key row
+// nkeys (the batch size) on (MASK_EDGE only:
 // the caller takes that variant for the tiles they fall into).  LOCAL (with STATS): the row sums and the label numerators
 // are added into rs / kept in ed (registers of the lane, indexed like ref2) instead of being written to lpart / ediag.
 // jl0: first key column of the tile relative to the panel of width W that p.E holds.  STREAM: streaming stores
@@ -231,11 +232,25 @@ __global__ __launch_bounds__(256) void k_pad_operands(const uint16_t* I, const u
 // for a caller that wants sums down its columns.
 constexpr int64_t NO_SELF = -((int64_t)1 << 40);
 
+// Do label columns or left-out columns of the 256 query rows from global row g on fall among key rows [j0, j0 + BM)?
+// (Only such tiles pay for finding those columns.  The rows of a tile of the two-view loss may lie in both views.)
+__device__ __forceinline__ bool tile_has_marked_columns(int64_t g, int64_t B, int variant, int64_t j0) {
+  auto hits = [&](int64_t lo, int64_t hi) { return lo < j0 + BM && j0 < hi; };      // key rows [lo, hi)
+  if (variant != LOSS_NTXENT) return hits(g, g + BN);
+  const int64_t M = B / 2;
+  bool h = hits(g, g + BN);                                                          // the rows' own columns
+  const int64_t hi1 = g + BN < M ? g + BN : M;                                       // rows of view one: label g' + M
+  if (g < hi1) h = h || hits(g + M, hi1 + M);
+  const int64_t lo2 = g > M ? g : M;                                                 // rows of view two: label g' - M
+  if (lo2 < g + BN) h = h || hits(lo2 - M, g + BN - M);
+  return h;
+}
+
 enum { MASK_NONE = 0, MASK_DIAG = 1, MASK_EDGE = 2 };     // MASK_EDGE: label / left-out columns and padding columns
 
 template <bool STATS, bool STORE, int MASK, bool LOCAL = false, bool STAGE = false, bool STREAM = true>
 __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)[4][2], char* smem, int64_t b, float s2, int64_t i0,
-                                               int64_t j0, int64_t lab0, int64_t self0, int64_t nkeys, const float (&ref2)[2],
+                                               int64_t j0, int64_t g0, int variant, int64_t nkeys, const float (&ref2)[2],
                                                int64_t jl0, int64_t W, float* rs = nullptr, float* ed = nullptr) {
   constexpr bool DIAG = MASK != MASK_NONE, EDGE = MASK == MASK_EDGE;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -247,9 +262,9 @@ __device__ __forceinline__ void logit_epilogue(const BlockPtrs& p, f32x16 (&acc)
     const float ref = ref2[bn];
     // label column of row i, relative to this lane's first key column of the tile (any value outside
     // [0, 128) means the label is not among this lane's columns)
-    const int64_t dl64 = lab0 + i - (j0 + wm * 128 + half * 4);
+    const int64_t dl64 = (DIAG ? label_row(g0 + i, nkeys, variant) : 0) - (j0 + wm * 128 + half * 4);
     const int dl = dl64 >= 0 && dl64 < 128 ? (int)dl64 : -1;
-    const int64_t dm64 = self0 + i - (j0 + wm * 128 + half * 4);
+    const int64_t dm64 = (variant == LOSS_NTXENT ? g0 + i : NO_SELF) - (j0 + wm * 128 + half * 4);
     const int dm = dm64 >= 0 && dm64 < 128 ? (int)dm64 : -1;
     // first padding column, relative like dl (128: none among this lane's columns)
     const int64_t jl64 = nkeys - (j0 + wm * 128 + half * 4);
@@ -390,14 +405,11 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_tiles(Blocks bl, int64_t b, 
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
 
-    // label of query row i is key row lab0 + i (one offset for the whole tile: tiles do not straddle the two views)
-    const int64_t lab0 = label_row(g0 + i0, B, bl.variant) - i0;
-    const int64_t self0 = bl.variant == LOSS_NTXENT ? g0 : NO_SELF;
     // Only the tiles that the label diagonal (or the left-out diagonal) crosses, or that hold padding columns, pay
     // for finding those columns.
-    const bool diag = ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) || ((self0 + i0 < j0 + BM) && (j0 < self0 + i0 + BN));
-    if (diag || (RAGGED && j0 + BM > B)) logit_epilogue<STATS, STORE, RAGGED ? MASK_EDGE : MASK_DIAG>(p, acc, smem, b, s2, i0, j0, lab0, self0, B, ref2, j0 - jp0, W);
-    else logit_epilogue<STATS, STORE, MASK_NONE>(p, acc, smem, b, s2, i0, j0, lab0, self0, B, ref2, j0 - jp0, W);
+    const bool diag = tile_has_marked_columns(g0 + i0, B, bl.variant, j0);
+    if (diag || (RAGGED && j0 + BM > B)) logit_epilogue<STATS, STORE, RAGGED ? MASK_EDGE : MASK_DIAG>(p, acc, smem, b, s2, i0, j0, g0, bl.variant, B, ref2, j0 - jp0, W);
+    else logit_epilogue<STATS, STORE, MASK_NONE>(p, acc, smem, b, s2, i0, j0, g0, bl.variant, B, ref2, j0 - jp0, W);
   }
 }
 
@@ -521,8 +533,7 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
   if (p.tileflag[it] == 0) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3, half = lane >> 5;
   const int64_t i0 = (int64_t)it * BN;
-  const int64_t lab0 = label_row((int64_t)rank * bl.rows + i0, B, bl.variant) - i0;
-  const int64_t self0 = bl.variant == LOSS_NTXENT ? (int64_t)rank * bl.rows : NO_SELF;
+  const int64_t g0 = (int64_t)rank * bl.rows;             // global row of the rank's first row
   float* red = reinterpret_cast<float*>(smem);            // [2][256] exchange between the two key halves
   f32x16 acc[4][2];
   float ref2[2] = {-INFINITY, -INFINITY};
@@ -536,12 +547,12 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
     mainloop<FMT_K, FMT_K, true>(p.Y + (int64_t)jt * BM * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
     const int64_t j0 = (int64_t)jt * BM;
     // the left-out column and the padding columns take no part in the maximum
-    const bool has_self = (self0 + i0 < j0 + BM) && (j0 < self0 + i0 + BN);
+    const bool has_self = bl.variant == LOSS_NTXENT && (g0 + i0 < j0 + BM) && (j0 < g0 + i0 + BN);
     const int64_t jl64 = bl.keys - (j0 + wm * 128 + half * 4);
     const int jlim = jl64 >= 128 ? 128 : jl64 > 0 ? (int)jl64 : 0;
 #pragma unroll
     for (int bn = 0; bn < 2; ++bn) {
-      const int64_t dm64 = self0 + i0 + wn * 64 + bn * 32 + (lane & 31) - (j0 + wm * 128 + half * 4);
+      const int64_t dm64 = g0 + i0 + wn * 64 + bn * 32 + (lane & 31) - (j0 + wm * 128 + half * 4);
 #pragma unroll
       for (int bm = 0; bm < 4; ++bm)
 #pragma unroll
@@ -576,10 +587,9 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     mainloop<FMT_K, FMT_K, true>(p.Y + j0 * d, d, p.X + i0 * d, d, (int)(d / BK), smem, acc);
-    const bool diag = ((lab0 + i0 < j0 + BM) && (j0 < lab0 + i0 + BN)) || ((self0 + i0 < j0 + BM) && (j0 < self0 + i0 + BN)) ||
-                      j0 + BM > bl.keys;
-    if (diag) logit_epilogue<true, STORE, MASK_EDGE, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, bl.keys, ref2, j0, B, rs, ed);
-    else logit_epilogue<true, STORE, MASK_NONE, true>(p, acc, smem, b, s2, i0, j0, lab0, self0, bl.keys, ref2, j0, B, rs, ed);
+    const bool diag = tile_has_marked_columns(g0 + i0, bl.keys, bl.variant, j0) || j0 + BM > bl.keys;
+    if (diag) logit_epilogue<true, STORE, MASK_EDGE, true>(p, acc, smem, b, s2, i0, j0, g0, bl.variant, bl.keys, ref2, j0, B, rs, ed);
+    else logit_epilogue<true, STORE, MASK_NONE, true>(p, acc, smem, b, s2, i0, j0, g0, bl.variant, bl.keys, ref2, j0, B, rs, ed);
   }
   // row totals: the four lanes (two key halves x two lane halves) that share a row; exactly one of them met the label
   __syncthreads();
@@ -733,7 +743,8 @@ __global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int64_t b, in
 // The second line lands in another row, lab.  If lab belongs to this rank too, the wave that owns it adds the term
 // (seen from there it reads gdiag_i' Z[lab'] with i' its positive, since the positive of the positive is the row
 // itself); otherwise the wave of row i writes it.  Every row of gZ so has exactly one writer in this kernel.
-__global__ __launch_bounds__(256) void k_query_finalize_ntxent(Blocks bl, int64_t b, int64_t B, int64_t d, int rank, float cs, int splitk) {
+// b: the real rows; bp: row pitch of the partial products.
+__global__ __launch_bounds__(256) void k_query_finalize_ntxent(Blocks bl, int64_t b, int64_t bp, int64_t B, int64_t d, int rank, float cs, int splitk) {
   if (gated_off(bl)) return;
   typedef __attribute__((ext_vector_type(4))) float f32x4;
   const BlockPtrs& p = bl.z[0];
@@ -748,7 +759,7 @@ __global__ __launch_bounds__(256) void k_query_finalize_ntxent(Blocks bl, int64_
   float dot = 0.f;
   for (int64_t k = lane * 4; k < d; k += 256) {
     f32x4 u = {0.f, 0.f, 0.f, 0.f};
-    for (int ks = 0; ks < splitk; ++ks) u += *reinterpret_cast<const f32x4*>(p.part + ((int64_t)ks * b + i) * d + k);
+    for (int ks = 0; ks < splitk; ++ks) u += *reinterpret_cast<const f32x4*>(p.part + ((int64_t)ks * bp + i) * d + k);
     const u32x2 zw = *reinterpret_cast<const u32x2*>(Zfull + g * d + k);        // Z[g]
     const u32x2 pw = *reinterpret_cast<const u32x2*>(Zfull + lab * d + k);      // Z[lab]
     const float zv[4] = {bf16_lo(zw[0]), bf16_hi(zw[0]), bf16_lo(zw[1]), bf16_hi(zw[1])};
@@ -860,8 +871,8 @@ __global__ __launch_bounds__(NTHREADS) void k_sym_logit(Blocks bl, int64_t B, in
     // the label of query row i is key row i: only the tiles on the diagonal contain label columns
     // (ordinary stores: the matrix is read again by the combining pass and the two contractions)
     if (it == jt || (RAGGED && j0 + BM > bl.keys))
-      logit_epilogue<true, true, RAGGED ? MASK_EDGE : MASK_DIAG, false, true, false>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, bl.keys, ref2, j0, B);
-    else logit_epilogue<true, true, MASK_NONE, false, true, false>(p, acc, smem, B, s2, i0, j0, 0, NO_SELF, bl.keys, ref2, j0, B);
+      logit_epilogue<true, true, RAGGED ? MASK_EDGE : MASK_DIAG, false, true, false>(p, acc, smem, B, s2, i0, j0, 0, LOSS_CLIP, bl.keys, ref2, j0, B);
+    else logit_epilogue<true, true, MASK_NONE, false, true, false>(p, acc, smem, B, s2, i0, j0, 0, LOSS_CLIP, bl.keys, ref2, j0, B);
     lds_barrier();
     const int t = threadIdx.x;
     const int chunk16 = t & 31, r0 = t >> 5;
@@ -1067,7 +1078,6 @@ int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_
   if (!lds_ok) return DISCO_ERR_HIP;
   const int nblk = loss_blocks(pr.variant);
   const Plan pl = make_plan(pr.B, pr.d, pr.N, fused, nblk);
-  if (pl.ragged && pr.variant != LOSS_CLIP) return DISCO_ERR_UNSUPPORTED;   // (the dispatch does not send these here)
   const int persistent_wgs = compute_units();
   const int64_t b = pl.b, B = pl.B, d = pl.d, W = pl.W;     // whole tiles; the real sizes are pl.b_real, pl.B_real
   char* ws = static_cast<char*>(pr.ws);
@@ -1173,7 +1183,7 @@ int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_
       k_query_partial<false><<<q_grid, NTHREADS, GEMM_SMEM_BYTES, st>>>(bl, b, d, jp0, W, pl.nMq, pl.nN, pl.splitk, pl.ktps);
   }
   if (marks) stage_mark(st, stage++);
-  if (pr.variant == LOSS_NTXENT) k_query_finalize_ntxent<<<dim3((unsigned)((b + 3) / 4)), 256, 0, st>>>(bl, b, B, d, pr.rank, cs, pl.splitk);
+  if (pr.variant == LOSS_NTXENT) k_query_finalize_ntxent<<<dim3((unsigned)((pl.b_real + 3) / 4)), 256, 0, st>>>(bl, pl.b_real, b, pl.B_real, d, pr.rank, cs, pl.splitk);
   else k_query_finalize<<<dim3((unsigned)((pl.b_real + 3) / 4)), 256, 0, st>>>(bl, pl.b_real, b, d, pr.rank, cs, pl.splitk);
   k_scalars<<<1, 1024, 0, st>>>(bl, pl.b_real, c, pr.accumulate, pr.loss, pr.gs);
   if (marks) stage_mark(st, stage++);
@@ -1297,8 +1307,7 @@ bool mfma_supported(int64_t B, int64_t d, int32_t N, int dtype, int variant) {
   if (dtype != DISCO_BF16) return false;
   if (N <= 0 || B % N != 0) return false;
   const int64_t b = B / N;
-  // two-view loss: a 256-row query tile must lie within one view, so that its labels are one offset away
-  if (variant == LOSS_NTXENT && (B % 2 != 0 || (B / 2) % 256 != 0 || b % 256 != 0)) return false;
+  if (variant == LOSS_NTXENT && B % 2 != 0) return false;                   // two views
   // per-lane load offsets are 32-bit byte offsets inside one operand tile: 256 rows of pitch b (Xs) or four block
   // rows of pitch 64 W (row groups of the stored numerators) must stay below 4 GiB
   if (B > ((int64_t)1 << 23) || b > ((int64_t)1 << 22)) return false;      // (rounding up to whole tiles stays within them)

@@ -109,10 +109,13 @@ def test_two_view_loss_argument_checks():
     assert call() == dl.DISCO_ERR_WORKSPACE                            # valid arguments, workspace too small
     need = dl.ntxent_workspace_bytes(256, 64, 4, dl.DISCO_F32, dl.DISCO_PATH_NAIVE)
     assert need >= 64 * 256 * 4 and need < 2 * 64 * 256 * 4 + 8192     # ONE b x B block (the CLIP loss keeps two)
-    # the bf16 tile paths need whole 256-row tiles inside one view
+    # the bf16 tile paths take any share (ragged ones padded); AUTO sends tiny ragged blocks to the fp32 path
     assert dl.ntxent_resolve_path(1024, 64, 2, dl.DISCO_BF16, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_MATERIALIZED
-    assert dl.ntxent_resolve_path(768, 64, 1, dl.DISCO_BF16, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
-    assert dl.ntxent_resolve_path(768, 64, 1, dl.DISCO_BF16, dl.DISCO_PATH_FUSED) == -dl.DISCO_ERR_UNSUPPORTED
+    assert dl.ntxent_resolve_path(1000, 64, 1, dl.DISCO_BF16, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_MATERIALIZED
+    assert dl.ntxent_resolve_path(1000, 64, 1, dl.DISCO_BF16, dl.DISCO_PATH_FUSED) == dl.DISCO_PATH_FUSED
+    assert dl.ntxent_resolve_path(100, 64, 2, dl.DISCO_BF16, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
+    assert dl.ntxent_resolve_path(1000, 65, 1, dl.DISCO_BF16, dl.DISCO_PATH_FUSED) == -dl.DISCO_ERR_UNSUPPORTED
+    assert dl.ntxent_resolve_path(1024, 64, 1, dl.DISCO_BF16, dl.DISCO_PATH_SYMMETRIC) == -dl.DISCO_ERR_UNSUPPORTED
     assert dl.ntxent_workspace_bytes(255, 64, 1, dl.DISCO_F32, dl.DISCO_PATH_NAIVE) == 0
 
 
@@ -174,5 +177,4 @@ def test_auto_sends_ragged_shares_to_the_tile_kernels_when_large_enough():
     assert dl.disco_resolve_path(1000, 100, 2, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE       # d % 64 != 0
     assert dl.disco_resolve_path(1000, 256, 1, dt, dl.DISCO_PATH_SYMMETRIC) == dl.DISCO_PATH_SYMMETRIC
     assert dl.disco_resolve_path(1000, 256, 2, dt, dl.DISCO_PATH_FUSED) == dl.DISCO_PATH_FUSED
-    assert dl.ntxent_resolve_path(1000, 256, 2, dt, dl.DISCO_PATH_FUSED) < 0          # the two-view loss: whole tiles only
     assert dl.disco_workspace_bytes(1000, 256, 2, dt, dl.DISCO_PATH_MATERIALIZED) > dl.disco_workspace_bytes(1024, 256, 2, dt, dl.DISCO_PATH_MATERIALIZED)

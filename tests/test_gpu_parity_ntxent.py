@@ -90,3 +90,26 @@ def test_two_view_loss_mfma_paths(path, M, d, N, s):
     ls, gsl, ss = slow.results()
     check_scalar("loss vs fp32 path", lf, ls, 1e-4)
     check_tensor("gZ vs fp32 path", gf, gsl, "bf16", nx.ntxent_rank_term_scale(Z, s, N - 1, N)[0], 1e-13 * s / B)
+
+
+@pytest.mark.parametrize("M,d,N,s", [(500, 256, 1, 14.285714),    # one ragged share holding both views: tiles straddle the views
+                                     (500, 128, 2, 14.285714),    # a rank per view, 500 rows each
+                                     (640, 64, 5, 25.0),          # 256-row shares of a batch whose views are not whole tiles
+                                     (770, 192, 4, 14.285714),    # 385-row shares; ranks 1 and 2 meet at the view boundary
+                                     (300, 64, 3, 14.285714),     # 200-row shares: rank 1 holds rows of both views
+                                     (1, 64, 1, 14.285714)])      # one sample, two views: each row's only negative is nothing
+@pytest.mark.parametrize("path", ["materialized", "fused"])
+def test_two_view_loss_mfma_paths_on_shares_that_are_not_whole_tiles(path, M, d, N, s):
+    """Shares, views and batches that are not whole 256-row tiles: operands padded in the workspace, the padding out of
+    every softmax, and query tiles whose rows belong to both views (two label offsets in one tile)."""
+    B = 2 * M
+    Z, Zd, dt = _inputs(M, d, 6, "bf16")
+    assert dl.ntxent_resolve_path(B, d, N, dt, PATHS[path]) == PATHS[path]
+    run = Run(Zd, B, d, N, dt, PATHS[path])
+    for r in range(N):
+        print(f"case two-view ragged {path} M={M} d={d} N={N} s={s} rank={r}", flush=True)
+        run.rank(r, s)
+        _compare(run, nx.ntxent_rank(Z, s, r, N), nx.ntxent_rank_term_scale(Z, s, r, N), "bf16", f"ragged {path} M{M} d{d} N{N} rank {r}", s, B)
+    for r in range(N):
+        run.rank(r, s, accumulate=(r > 0))
+    _compare(run, nx.ntxent_full(Z, s), nx.ntxent_rank_term_scale(Z, s, 0, 1), "bf16", f"ragged {path} M{M} d{d} N{N} accumulated", s, B)
