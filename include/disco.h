@@ -54,7 +54,7 @@ extern "C" {
 typedef enum {
   DISCO_OK = 0,
   DISCO_ERR_NULL = 1,        /* a required pointer is NULL */
-  DISCO_ERR_SHAPE = 2,       /* B<=0, d<=0, N<=0, B % N != 0, rank outside [0,N), B > 2^24, d > 2^16, B/N > 2^22 */
+  DISCO_ERR_SHAPE = 2,       /* B<=0, d<=0, N<=0, B % N != 0, rank outside [0,N), B > 2^24, d > 2^16, B/N > 65535*64 */
   DISCO_ERR_UNSUPPORTED = 3, /* unknown dtype/path value, the path cannot run this shape/dtype, or a bf16 MFMA
                                 path was handed I, T, gI or gT that is not 16-byte aligned */
   DISCO_ERR_WORKSPACE = 4,   /* workspace NULL/misaligned or smaller than disco_workspace_bytes() */

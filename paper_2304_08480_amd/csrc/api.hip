@@ -33,7 +33,7 @@ int check_shape(int64_t B, int64_t d, int32_t N) {
   // tile indices and row offsets are kept in 32-bit registers inside the kernels
   if (B > (int64_t)1 << 24 || d > (int64_t)1 << 16) return DISCO_ERR_SHAPE;
   // the fp32 path walks the rank's rows in 64-row tiles along a grid dimension limited to 65535 workgroups
-  if (B / N > (int64_t)1 << 22) return DISCO_ERR_SHAPE;
+  if (B / N > (int64_t)65535 * 64) return DISCO_ERR_SHAPE;
   return DISCO_OK;
 }
 

@@ -7,8 +7,6 @@
 namespace disco {
 namespace {
 
-constexpr int TS = 64;   // output tile edge of the tiled products
-constexpr int TK = 16;   // reduction step
 
 __device__ __forceinline__ float load_feat(const void* base, int dtype, int64_t idx) {
   if (dtype == DISCO_BF16) {
@@ -18,48 +16,95 @@ __device__ __forceinline__ float load_feat(const void* base, int dtype, int64_t 
   return static_cast<const float*>(base)[idx];
 }
 
-// Generic tiled product  out(m,n) = sum_k A(m,k) * Bm(k,n)  for one 64x64 output tile.
-// A and Bm are accessor functors returning 0 outside their range.  256 threads, 4x4 per thread.
-template <class FA, class FB, class FOut>
+// Generic tiled product  out(m,n) = sum_k A(m,k) * Bm(k,n)  for one TM x TN output tile (TM, TN: 64 or 128).
+// A and Bm are accessor functors (any layout, any dtype); entries outside the ranges count as 0.  256 threads as
+// 16 x 16; a thread owns (TM/16) x (TN/16) outputs in pieces of 4: rows ty*4 + u (+ 64 for the second piece), columns
+// tx*4 + v (+ 64), so that its LDS reads are 16-byte vectors, a wave's column reads are 256 contiguous bytes and
+// its row reads 4 broadcast pieces: one LDS read per 8 (128 x 128: 16) multiply-adds.
+// TK: reduction step.  PREFETCH: fetch the next reduction step's operand pieces into registers while the current one
+// is multiplied: pays where few workgroups share a compute unit (the query-side product), costs occupancy where
+// many do.
+template <int TM, int TN, int TK, bool PREFETCH, class FA, class FB, class FOut>
 __device__ __forceinline__ void tile_product(int64_t M, int64_t Nn, int64_t K, int64_t m0, int64_t n0,
                                              FA A, FB Bm, FOut out) {
-  __shared__ float As[TK][TS + 1];
-  __shared__ float Bs[TK][TS + 1];
+  typedef __attribute__((ext_vector_type(4))) float f32x4;
+  constexpr int PM = TM / 64, PN = TN / 64;             // pieces of 4 rows / columns per thread
+  __shared__ __attribute__((aligned(16))) float As[TK][TM + 4];
+  __shared__ __attribute__((aligned(16))) float Bs[TK][TN + 4];
   const int tid = threadIdx.x;
   const int tx = tid % 16, ty = tid / 16;
-  float acc[4][4] = {};
-  for (int64_t k0 = 0; k0 < K; k0 += TK) {
-    for (int e = tid; e < TS * TK; e += 256) {
-      int kk = e % TK, mm = e / TK;
-      int64_t m = m0 + mm, k = k0 + kk;
-      As[kk][mm] = (m < M && k < K) ? A(m, k) : 0.f;
+  float acc[PM * 4][PN * 4] = {};
+  constexpr int NA = TM * TK / 256, NB = TN * TK / 256;
+  float ra[NA], rb[NB];
+  auto fetch = [&](int64_t k0) {
+#pragma unroll
+    for (int r = 0; r < NA; ++r) {
+      const int e = tid + r * 256, kk = e % TK, mm = e / TK;
+      const int64_t m = m0 + mm, k = k0 + kk;
+      ra[r] = (m < M && k < K) ? A(m, k) : 0.f;
     }
-    for (int e = tid; e < TS * TK; e += 256) {
-      int nn = e % TS, kk = e / TS;
-      int64_t n = n0 + nn, k = k0 + kk;
-      Bs[kk][nn] = (n < Nn && k < K) ? Bm(k, n) : 0.f;
+#pragma unroll
+    for (int r = 0; r < NB; ++r) {
+      const int e = tid + r * 256, nn = e % TN, kk = e / TN;
+      const int64_t n = n0 + nn, k = k0 + kk;
+      rb[r] = (n < Nn && k < K) ? Bm(k, n) : 0.f;
+    }
+  };
+  if constexpr (PREFETCH) fetch(0);
+  for (int64_t k0 = 0; k0 < K; k0 += TK) {
+    if constexpr (PREFETCH) {
+#pragma unroll
+      for (int r = 0; r < NA; ++r) {
+        const int e = tid + r * 256;
+        As[e % TK][e / TK] = ra[r];
+      }
+#pragma unroll
+      for (int r = 0; r < NB; ++r) {
+        const int e = tid + r * 256;
+        Bs[e / TN][e % TN] = rb[r];
+      }
+    } else {
+      for (int e = tid; e < TM * TK; e += 256) {
+        const int kk = e % TK, mm = e / TK;
+        const int64_t m = m0 + mm, k = k0 + kk;
+        As[kk][mm] = (m < M && k < K) ? A(m, k) : 0.f;
+      }
+      for (int e = tid; e < TK * TN; e += 256) {
+        const int nn = e % TN, kk = e / TN;
+        const int64_t n = n0 + nn, k = k0 + kk;
+        Bs[kk][nn] = (n < Nn && k < K) ? Bm(k, n) : 0.f;
+      }
     }
     __syncthreads();
+    if constexpr (PREFETCH) { if (k0 + TK < K) fetch(k0 + TK); }
 #pragma unroll
     for (int kk = 0; kk < TK; ++kk) {
-      float a[4], bb[4];
+      f32x4 a[PM], bb[PN];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { a[u] = As[kk][ty * 4 + u]; bb[u] = Bs[kk][tx * 4 + u]; }
+      for (int p = 0; p < PM; ++p) a[p] = *reinterpret_cast<const f32x4*>(&As[kk][p * 64 + ty * 4]);
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int p = 0; p < PN; ++p) bb[p] = *reinterpret_cast<const f32x4*>(&Bs[kk][p * 64 + tx * 4]);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) acc[u][v] = fmaf(a[u], bb[v], acc[u][v]);
+      for (int u = 0; u < PM * 4; ++u)
+#pragma unroll
+        for (int v = 0; v < PN * 4; ++v) acc[u][v] = fmaf(a[u / 4][u % 4], bb[v / 4][v % 4], acc[u][v]);
     }
     __syncthreads();
   }
 #pragma unroll
-  for (int u = 0; u < 4; ++u)
+  for (int u = 0; u < PM * 4; ++u)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      int64_t m = m0 + ty * 4 + u, n = n0 + tx * 4 + v;
+    for (int v = 0; v < PN * 4; ++v) {
+      int64_t m = m0 + (u / 4) * 64 + ty * 4 + u % 4, n = n0 + (v / 4) * 64 + tx * 4 + v % 4;
       if (m < M && n < Nn) out(m, n, acc[u][v]);
     }
 }
+
+// Output tile edges of the three products: 128 x 128 where the grid is large (b x B similarities, B x d key-side
+// gradient), 64 x 64 for the b x d query-side gradient, whose grid would not fill the chip otherwise; that one
+// streams the b x B matrix along its rows, in 256-byte pieces (reduction step 64).
+constexpr int TS = 128;
+constexpr int TQ = 64;
 
 struct BlockView {
   const void* X;   // b x d local rows (already offset to the rank's first row)
@@ -84,7 +129,7 @@ __global__ __launch_bounds__(256) void naive_similarity(const void* I, const voi
                                                          int64_t B, int64_t d, int rank, float* ws) {
   BlockView v = block_view(I, T, dtype, b, B, d, rank, ws, blockIdx.z);
   int64_t m0 = (int64_t)blockIdx.y * TS, n0 = (int64_t)blockIdx.x * TS;
-  tile_product(
+  tile_product<TS, TS, 16, false>(
       b, B, d, m0, n0, [&](int64_t m, int64_t k) { return load_feat(v.X, dtype, m * d + k); },
       [&](int64_t k, int64_t n) { return load_feat(v.Y, dtype, n * d + k); },
       [&](int64_t m, int64_t n, float a) { v.W[m * B + n] = a; });
@@ -173,7 +218,7 @@ __global__ __launch_bounds__(256) void naive_key_grad(const void* I, const void*
   float* out = z == 0 ? gT : gI;
   // the B key rows run along grid.x (up to 2^31 - 1 workgroups), the feature columns along grid.y
   int64_t m0 = (int64_t)blockIdx.x * TS, n0 = (int64_t)blockIdx.y * TS;
-  tile_product(
+  tile_product<TS, TS, 16, false>(
       B, d, b, m0, n0, [&](int64_t m, int64_t k) { return v.W[k * B + m]; },
       [&](int64_t k, int64_t n) { return load_feat(v.X, dtype, k * d + n); },
       [&](int64_t m, int64_t n, float a) {
@@ -192,8 +237,8 @@ __global__ __launch_bounds__(256) void naive_query_grad(const void* I, const voi
   const int z = blockIdx.z;
   BlockView v = block_view(I, T, dtype, b, B, d, rank, ws, z);
   float* out = (z == 0 ? gI : gT) + (size_t)rank * b * d;
-  int64_t m0 = (int64_t)blockIdx.y * TS, n0 = (int64_t)blockIdx.x * TS;
-  tile_product(
+  int64_t m0 = (int64_t)blockIdx.y * TQ, n0 = (int64_t)blockIdx.x * TQ;
+  tile_product<TQ, TQ, 16, true>(
       b, d, B, m0, n0, [&](int64_t m, int64_t k) { return v.W[m * B + k]; },
       [&](int64_t k, int64_t n) { return load_feat(v.Y, dtype, k * d + n); },
       [&](int64_t m, int64_t n, float a) { out[m * d + n] += cs * a; });
@@ -230,7 +275,7 @@ int naive_run(const Problem& p) {
   naive_key_grad<<<dim3(cdiv(B, TS), cdiv(d, TS), nb), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,
                                                                           p.accumulate, p.gI, p.gT);
   stage_mark(p.stream, 4);
-  naive_query_grad<<<dim3(cdiv(d, TS), cdiv(b, TS), nb), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,
+  naive_query_grad<<<dim3(cdiv(d, TQ), cdiv(b, TQ), nb), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,
                                                                             p.gI, p.gT);
   stage_mark(p.stream, 5);
   return hipGetLastError() == hipSuccess ? DISCO_OK : DISCO_ERR_HIP;
