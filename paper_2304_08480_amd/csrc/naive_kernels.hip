@@ -21,10 +21,12 @@ __device__ __forceinline__ float load_feat(const void* base, int dtype, int64_t 
 // 16 x 16; a thread owns (TM/16) x (TN/16) outputs in pieces of 4: rows ty*4 + u (+ 64 for the second piece), columns
 // tx*4 + v (+ 64), so that its LDS reads are 16-byte vectors, a wave's column reads are 256 contiguous bytes and
 // its row reads 4 broadcast pieces: one LDS read per 8 (128 x 128: 16) multiply-adds.
-// TK: reduction step.  PREFETCH: fetch the next reduction step's operand pieces into registers while the current one
+// TK: reduction step.  AK / BK: the reduction index is the contiguous one in the memory behind A(m, k) / Bm(k, n);
+// the fill loops run consecutive threads along it, otherwise along m / n, so that the loads coalesce either way.
+// PREFETCH: fetch the next reduction step's operand pieces into registers while the current one
 // is multiplied: pays where few workgroups share a compute unit (the query-side product), costs occupancy where
 // many do.
-template <int TM, int TN, int TK, bool PREFETCH, class FA, class FB, class FOut>
+template <int TM, int TN, int TK, bool AK, bool BK, bool PREFETCH, class FA, class FB, class FOut>
 __device__ __forceinline__ void tile_product(int64_t M, int64_t Nn, int64_t K, int64_t m0, int64_t n0,
                                              FA A, FB Bm, FOut out) {
   typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -39,13 +41,13 @@ __device__ __forceinline__ void tile_product(int64_t M, int64_t Nn, int64_t K, i
   auto fetch = [&](int64_t k0) {
 #pragma unroll
     for (int r = 0; r < NA; ++r) {
-      const int e = tid + r * 256, kk = e % TK, mm = e / TK;
+      const int e = tid + r * 256, kk = AK ? e % TK : e / TM, mm = AK ? e / TK : e % TM;
       const int64_t m = m0 + mm, k = k0 + kk;
       ra[r] = (m < M && k < K) ? A(m, k) : 0.f;
     }
 #pragma unroll
     for (int r = 0; r < NB; ++r) {
-      const int e = tid + r * 256, nn = e % TN, kk = e / TN;
+      const int e = tid + r * 256, kk = BK ? e % TK : e / TN, nn = BK ? e / TK : e % TN;
       const int64_t n = n0 + nn, k = k0 + kk;
       rb[r] = (n < Nn && k < K) ? Bm(k, n) : 0.f;
     }
@@ -56,21 +58,21 @@ __device__ __forceinline__ void tile_product(int64_t M, int64_t Nn, int64_t K, i
 #pragma unroll
       for (int r = 0; r < NA; ++r) {
         const int e = tid + r * 256;
-        As[e % TK][e / TK] = ra[r];
+        As[AK ? e % TK : e / TM][AK ? e / TK : e % TM] = ra[r];
       }
 #pragma unroll
       for (int r = 0; r < NB; ++r) {
         const int e = tid + r * 256;
-        Bs[e / TN][e % TN] = rb[r];
+        Bs[BK ? e % TK : e / TN][BK ? e / TK : e % TN] = rb[r];
       }
     } else {
       for (int e = tid; e < TM * TK; e += 256) {
-        const int kk = e % TK, mm = e / TK;
+        const int kk = AK ? e % TK : e / TM, mm = AK ? e / TK : e % TM;
         const int64_t m = m0 + mm, k = k0 + kk;
         As[kk][mm] = (m < M && k < K) ? A(m, k) : 0.f;
       }
       for (int e = tid; e < TK * TN; e += 256) {
-        const int nn = e % TN, kk = e / TN;
+        const int kk = BK ? e % TK : e / TN, nn = BK ? e / TK : e % TN;
         const int64_t n = n0 + nn, k = k0 + kk;
         Bs[kk][nn] = (n < Nn && k < K) ? Bm(k, n) : 0.f;
       }
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(256) void naive_similarity(const void* I, const voi
                                                          int64_t B, int64_t d, int rank, float* ws) {
   BlockView v = block_view(I, T, dtype, b, B, d, rank, ws, blockIdx.z);
   int64_t m0 = (int64_t)blockIdx.y * TS, n0 = (int64_t)blockIdx.x * TS;
-  tile_product<TS, TS, 16, false>(
+  tile_product<TS, TS, 16, true, true, false>(
       b, B, d, m0, n0, [&](int64_t m, int64_t k) { return load_feat(v.X, dtype, m * d + k); },
       [&](int64_t k, int64_t n) { return load_feat(v.Y, dtype, n * d + k); },
       [&](int64_t m, int64_t n, float a) { v.W[m * B + n] = a; });
@@ -218,7 +220,7 @@ __global__ __launch_bounds__(256) void naive_key_grad(const void* I, const void*
   float* out = z == 0 ? gT : gI;
   // the B key rows run along grid.x (up to 2^31 - 1 workgroups), the feature columns along grid.y
   int64_t m0 = (int64_t)blockIdx.x * TS, n0 = (int64_t)blockIdx.y * TS;
-  tile_product<TS, TS, 16, false>(
+  tile_product<TS, TS, 16, true, false, false>(
       B, d, b, m0, n0, [&](int64_t m, int64_t k) { return v.W[k * B + m]; },
       [&](int64_t k, int64_t n) { return load_feat(v.X, dtype, k * d + n); },
       [&](int64_t m, int64_t n, float a) {
@@ -238,7 +240,7 @@ __global__ __launch_bounds__(256) void naive_query_grad(const void* I, const voi
   BlockView v = block_view(I, T, dtype, b, B, d, rank, ws, z);
   float* out = (z == 0 ? gI : gT) + (size_t)rank * b * d;
   int64_t m0 = (int64_t)blockIdx.y * TQ, n0 = (int64_t)blockIdx.x * TQ;
-  tile_product<TQ, TQ, 16, true>(
+  tile_product<TQ, TQ, 16, true, false, true>(
       b, d, B, m0, n0, [&](int64_t m, int64_t k) { return v.W[m * B + k]; },
       [&](int64_t k, int64_t n) { return load_feat(v.Y, dtype, k * d + n); },
       [&](int64_t m, int64_t n, float a) { out[m * d + n] += cs * a; });
