@@ -694,25 +694,42 @@ __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b
 //   gI[lab] += cs (beta^A_i sum_ks part^A + gdiag^A_i T[lab])    query side of block A (Eq. 4)
 //            + cs gdiag^C_i T[lab]                                label-column term of block C's key side
 //   gT[lab] += cs (beta^C_i sum_ks part^C + gdiag^C_i I[lab]) + cs gdiag^A_i I[lab]
-// and the rows' shares of d/ds, <query-side vector, x_i>, per block.  One wave per row, fixed summation order.
+// and the rows' shares of d/ds, <query-side vector, x_i>, per block.  Fixed summation order.  One wave per row; ROWWG
+// (small shares, where rows / 4 workgroups would leave most of the chip idle while each wave walks all the split-K
+// slices): one workgroup per row, its four waves each add every fourth slice and wave 0 combines them.
 // b: the real rows; bp: row pitch of the partial products.
+template <bool ROWWG>
 __global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int64_t b, int64_t bp, int64_t d, int rank, float cs, int splitk) {
   if (gated_off(bl)) return;
   typedef __attribute__((ext_vector_type(4))) float f32x4;
+  __shared__ f32x4 others[ROWWG ? 3 : 1][2][64];
   const BlockPtrs& pa = bl.z[0];
   const BlockPtrs& pc = bl.z[1];
-  const int lane = threadIdx.x & 63;
-  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (i >= b) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t i = ROWWG ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
+  if (i >= b) return;                                   // ROWWG: the whole workgroup
   const int64_t lab = (int64_t)rank * b + i;
   const float beta_a = pa.beta[i], gd_a = pa.gdiag[i], beta_c = pc.beta[i], gd_c = pc.gdiag[i];
   float dot_a = 0.f, dot_c = 0.f;
-  for (int64_t k = lane * 4; k < d; k += 256) {
+  for (int64_t kc = 0; kc < d; kc += 256) {
+    const int64_t k = kc + lane * 4;
+    const bool on = k < d;
     f32x4 ua = {0.f, 0.f, 0.f, 0.f}, uc = {0.f, 0.f, 0.f, 0.f};
-    for (int ks = 0; ks < splitk; ++ks) {
-      ua += *reinterpret_cast<const f32x4*>(pa.part + ((int64_t)ks * bp + i) * d + k);
-      uc += *reinterpret_cast<const f32x4*>(pc.part + ((int64_t)ks * bp + i) * d + k);
+    if (on)
+      for (int ks = ROWWG ? wave : 0; ks < splitk; ks += ROWWG ? 4 : 1) {
+        ua += *reinterpret_cast<const f32x4*>(pa.part + ((int64_t)ks * bp + i) * d + k);
+        uc += *reinterpret_cast<const f32x4*>(pc.part + ((int64_t)ks * bp + i) * d + k);
+      }
+    if (ROWWG) {
+      if (wave > 0) { others[wave - 1][0][lane] = ua; others[wave - 1][1][lane] = uc; }
+      __syncthreads();
+      if (wave == 0)
+#pragma unroll
+        for (int w = 0; w < 3; ++w) { ua += others[w][0][lane]; uc += others[w][1][lane]; }
+      __syncthreads();                                  // read before the next piece overwrites it
+      if (wave > 0) continue;
     }
+    if (!on) continue;
     const u32x2 iw = *reinterpret_cast<const u32x2*>(pa.X + i * d + k);        // I[lab]
     const u32x2 tw = *reinterpret_cast<const u32x2*>(pc.X + i * d + k);        // T[lab]
     const float iv[4] = {bf16_lo(iw[0]), bf16_hi(iw[0]), bf16_lo(iw[1]), bf16_hi(iw[1])};
@@ -731,10 +748,14 @@ __global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int64_t b, in
     *reinterpret_cast<f32x4*>(pa.gq + lab * d + k) = gi;
     *reinterpret_cast<f32x4*>(pc.gq + lab * d + k) = gt;
   }
+  if (ROWWG && wave > 0) return;
   dot_a = wave_sum(dot_a);
   dot_c = wave_sum(dot_c);
   if (lane == 0) { pa.rowds[i] = dot_a; pc.rowds[i] = dot_c; }
 }
+
+// shares up to this many rows finalize with one workgroup per row
+constexpr int64_t FINALIZE_ROWWG_MAX = 1024;
 
 // The same for the two-view loss (one block, X = Y = Z, gq = gk = gZ).  With g = rank b + i the row's own global row
 // and lab its positive's row:
@@ -1184,7 +1205,8 @@ int mfma_run(const Problem& pr, bool fused, const int* gate = nullptr, int gate_
   }
   if (marks) stage_mark(st, stage++);
   if (pr.variant == LOSS_NTXENT) k_query_finalize_ntxent<<<dim3((unsigned)((pl.b_real + 3) / 4)), 256, 0, st>>>(bl, pl.b_real, b, pl.B_real, d, pr.rank, cs, pl.splitk);
-  else k_query_finalize<<<dim3((unsigned)((pl.b_real + 3) / 4)), 256, 0, st>>>(bl, pl.b_real, b, d, pr.rank, cs, pl.splitk);
+  else if (pl.b_real <= FINALIZE_ROWWG_MAX) k_query_finalize<true><<<dim3((unsigned)pl.b_real), 256, 0, st>>>(bl, pl.b_real, b, d, pr.rank, cs, pl.splitk);
+  else k_query_finalize<false><<<dim3((unsigned)((pl.b_real + 3) / 4)), 256, 0, st>>>(bl, pl.b_real, b, d, pr.rank, cs, pl.splitk);
   k_scalars<<<1, 1024, 0, st>>>(bl, pl.b_real, c, pr.accumulate, pr.loss, pr.gs);
   if (marks) stage_mark(st, stage++);
   return hipGetLastError() == hipSuccess ? DISCO_OK : DISCO_ERR_HIP;
