@@ -30,10 +30,13 @@ PAPER_SAMPLES_PER_S = {"b32k_n64": 512 / 4.4e-3}
 PATH_NAMES = {1: "naive", 2: "materialized", 3: "fused", 4: "symmetric"}
 
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs whose
-# summary is profiles/b32k_n8_hbm_traffic.txt (counters cannot be read from inside this process; the fetch part
-# varies by about a quarter from run to run with what the last-level cache still holds).  Only the headline
-# workload has such a summary: every other workload and path reports null on purpose.
-MEASURED_TRAFFIC_BYTES = {("b32k_n8", "materialized", "logit_tiles"): 8.973e8}
+# summaries are profiles/<workload>_hbm_traffic.txt (counters cannot be read from inside this process; the fetch
+# part varies by about a quarter from run to run with what the last-level cache still holds).  Workloads and
+# paths without such a summary report null on purpose.
+MEASURED_TRAFFIC_BYTES = {("b32k_n8", "materialized", "logit_tiles"): 8.962e8,
+                          ("b196k_n64", "materialized", "logit_tiles"): 3.509e9,
+                          ("b64k_d768_n8", "materialized", "logit_tiles"): 4.590e9,
+                          ("full_n1", "symmetric", "logit_tiles_row_and_column_sums"): 3.930e9}
 
 
 def parse():
