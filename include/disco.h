@@ -103,7 +103,7 @@ typedef enum {
   DISCO_PATH_SYMMETRIC = 4
 } disco_path;
 
-/* The concrete path (1..3) that `path` resolves to for these arguments, or a negative
+/* The concrete path (1..4) that `path` resolves to for these arguments, or a negative
  * disco_status (e.g. -DISCO_ERR_UNSUPPORTED) if the arguments are invalid for it.  Host only. */
 DISCO_API int disco_resolve_path(int64_t B, int64_t d, int32_t N, int dtype, int path);
 

@@ -103,8 +103,8 @@ __device__ __forceinline__ void tile_product(int64_t M, int64_t Nn, int64_t K, i
 }
 
 // Output tile edges of the three products: 128 x 128 where the grid is large (b x B similarities, B x d key-side
-// gradient), 64 x 64 for the b x d query-side gradient, whose grid would not fill the chip otherwise; that one
-// streams the b x B matrix along its rows, in 256-byte pieces (reduction step 64).
+// gradient), 64 x 64 for the b x d query-side gradient, whose grid would not fill the chip otherwise (it prefetches
+// the next reduction step while it multiplies).  Reduction step 16 everywhere.
 constexpr int TS = 128;
 constexpr int TQ = 64;
 
