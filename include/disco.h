@@ -65,9 +65,9 @@ typedef enum {
 typedef enum { DISCO_F32 = 0, DISCO_BF16 = 1 } disco_dtype;
 
 /*
- * DISCO_PATH_NAIVE        fp32 FMA arithmetic on the vector ALUs, fp32 logit blocks kept in the
- *                         workspace (2*b*B*4 bytes: the paper's 2B^2/N memory model, Sec. 4.1).
- *                         Any B, d, N; either dtype.
+ * DISCO_PATH_NAIVE        fp32 arithmetic (fp32 matrix instruction for fp32 features, vector-ALU FMA for
+ *                         part of the bf16 case), fp32 logit blocks kept in the workspace (2*b*B*4
+ *                         bytes: the paper's 2B^2/N memory model, Sec. 4.1).  Any B, d, N; either dtype.
  * DISCO_PATH_MATERIALIZED bf16 MFMA tiles.  The logit blocks are computed once; the un-normalised
  *                         softmax numerators are kept in bf16 (2*b*B*2 bytes) and feed the two
  *                         gradient contractions (12*b*B*d flop).  Needs dtype bf16, d % 64 == 0,

@@ -1,4 +1,4 @@
-// Reference-grade GPU path: fp32 FMA arithmetic on the vector ALUs, any shape, either input dtype.
+// Reference-grade GPU path: fp32 arithmetic (fp32 matrix instruction or vector-ALU FMA), any shape, either input dtype.
 // The two b x B blocks of raw similarities live in the workspace in fp32 (the 2B^2/N memory model
 // of Sec. 4.1) and are turned in place into (softmax - onehot); the four gradient contractions of
 // Eq. 4-6 are plain tiled products.  Everything is deterministic (no float atomics).
@@ -8,27 +8,27 @@ namespace disco {
 namespace {
 
 
-__device__ __forceinline__ float load_feat(const void* base, int dtype, int64_t idx) {
-  if (dtype == DISCO_BF16) {
+// DT: DISCO_F32 or DISCO_BF16, a template argument of the product kernels so that no load sits behind a branch
+// (the fill loops then issue all their loads before they wait for the first).
+template <int DT>
+__device__ __forceinline__ float load_feat(const void* base, int64_t idx) {
+  if (DT == DISCO_BF16) {
     uint32_t u = static_cast<const uint16_t*>(base)[idx];
     return __uint_as_float(u << 16);
   }
   return static_cast<const float*>(base)[idx];
 }
 
-// Generic tiled product  out(m,n) = sum_k A(m,k) * Bm(k,n)  for one TM x TN output tile (TM, TN: 64 or 128).
-// A and Bm are accessor functors (any layout, any dtype); entries outside the ranges count as 0.  256 threads as
-// 16 x 16; a thread owns (TM/16) x (TN/16) outputs in pieces of 4: rows ty*4 + u (+ 64 for the second piece), columns
-// tx*4 + v (+ 64), so that its LDS reads are 16-byte vectors, a wave's column reads are 256 contiguous bytes and
-// its row reads 4 broadcast pieces: one LDS read per 8 (128 x 128: 16) multiply-adds.
+// Generic tiled product  out(m,n) = sum_k A(m,k) * Bm(k,n)  for one TM x TN output tile (TM, TN: 64 or 128), on the
+// vector ALUs.  A and Bm are accessor functors (any layout, any dtype); entries outside the ranges count as 0.
+// 256 threads as 16 x 16; a thread owns (TM/16) x (TN/16) outputs in pieces of 4: rows ty*4 + u (+ 64 for the second
+// piece), columns tx*4 + v (+ 64), so that its LDS reads are 16-byte vectors, a wave's column reads are 256
+// contiguous bytes and its row reads 4 broadcast pieces: one LDS read per 8 (128 x 128: 16) multiply-adds.
 // TK: reduction step.  AK / BK: the reduction index is the contiguous one in the memory behind A(m, k) / Bm(k, n);
 // the fill loops run consecutive threads along it, otherwise along m / n, so that the loads coalesce either way.
-// PREFETCH: fetch the next reduction step's operand pieces into registers while the current one
-// is multiplied: pays where few workgroups share a compute unit (the query-side product), costs occupancy where
-// many do.
-template <int TM, int TN, int TK, bool AK, bool BK, bool PREFETCH, class FA, class FB, class FOut>
-__device__ __forceinline__ void tile_product(int64_t M, int64_t Nn, int64_t K, int64_t m0, int64_t n0,
-                                             FA A, FB Bm, FOut out) {
+template <int TM, int TN, int TK, bool AK, bool BK, class FA, class FB, class FOut>
+__device__ __forceinline__ void tile_product_valu(int64_t M, int64_t Nn, int64_t K, int64_t m0, int64_t n0,
+                                                  FA A, FB Bm, FOut out) {
   typedef __attribute__((ext_vector_type(4))) float f32x4;
   constexpr int PM = TM / 64, PN = TN / 64;             // pieces of 4 rows / columns per thread
   __shared__ __attribute__((aligned(16))) float As[TK][TM + 4];
@@ -36,49 +36,18 @@ __device__ __forceinline__ void tile_product(int64_t M, int64_t Nn, int64_t K, i
   const int tid = threadIdx.x;
   const int tx = tid % 16, ty = tid / 16;
   float acc[PM * 4][PN * 4] = {};
-  constexpr int NA = TM * TK / 256, NB = TN * TK / 256;
-  float ra[NA], rb[NB];
-  auto fetch = [&](int64_t k0) {
-#pragma unroll
-    for (int r = 0; r < NA; ++r) {
-      const int e = tid + r * 256, kk = AK ? e % TK : e / TM, mm = AK ? e / TK : e % TM;
-      const int64_t m = m0 + mm, k = k0 + kk;
-      ra[r] = (m < M && k < K) ? A(m, k) : 0.f;
-    }
-#pragma unroll
-    for (int r = 0; r < NB; ++r) {
-      const int e = tid + r * 256, kk = BK ? e % TK : e / TN, nn = BK ? e / TK : e % TN;
-      const int64_t n = n0 + nn, k = k0 + kk;
-      rb[r] = (n < Nn && k < K) ? Bm(k, n) : 0.f;
-    }
-  };
-  if constexpr (PREFETCH) fetch(0);
   for (int64_t k0 = 0; k0 < K; k0 += TK) {
-    if constexpr (PREFETCH) {
-#pragma unroll
-      for (int r = 0; r < NA; ++r) {
-        const int e = tid + r * 256;
-        As[AK ? e % TK : e / TM][AK ? e / TK : e % TM] = ra[r];
-      }
-#pragma unroll
-      for (int r = 0; r < NB; ++r) {
-        const int e = tid + r * 256;
-        Bs[BK ? e % TK : e / TN][BK ? e / TK : e % TN] = rb[r];
-      }
-    } else {
-      for (int e = tid; e < TM * TK; e += 256) {
-        const int kk = AK ? e % TK : e / TM, mm = AK ? e / TK : e % TM;
-        const int64_t m = m0 + mm, k = k0 + kk;
-        As[kk][mm] = (m < M && k < K) ? A(m, k) : 0.f;
-      }
-      for (int e = tid; e < TK * TN; e += 256) {
-        const int kk = BK ? e % TK : e / TN, nn = BK ? e / TK : e % TN;
-        const int64_t n = n0 + nn, k = k0 + kk;
-        Bs[kk][nn] = (n < Nn && k < K) ? Bm(k, n) : 0.f;
-      }
+    for (int e = tid; e < TM * TK; e += 256) {
+      const int kk = AK ? e % TK : e / TM, mm = AK ? e / TK : e % TM;
+      const int64_t m = m0 + mm, k = k0 + kk;
+      As[kk][mm] = (m < M && k < K) ? A(m, k) : 0.f;
+    }
+    for (int e = tid; e < TK * TN; e += 256) {
+      const int kk = BK ? e % TK : e / TN, nn = BK ? e / TK : e % TN;
+      const int64_t n = n0 + nn, k = k0 + kk;
+      Bs[kk][nn] = (n < Nn && k < K) ? Bm(k, n) : 0.f;
     }
     __syncthreads();
-    if constexpr (PREFETCH) { if (k0 + TK < K) fetch(k0 + TK); }
 #pragma unroll
     for (int kk = 0; kk < TK; ++kk) {
       f32x4 a[PM], bb[PN];
@@ -102,11 +71,101 @@ __device__ __forceinline__ void tile_product(int64_t M, int64_t Nn, int64_t K, i
     }
 }
 
-// Output tile edges of the three products: 128 x 128 where the grid is large (b x B similarities, B x d key-side
-// gradient), 64 x 64 for the b x d query-side gradient, whose grid would not fill the chip otherwise (it prefetches
-// the next reduction step while it multiplies).  Reduction step 16 everywhere.
+// The same product on the matrix cores in fp32 (v_mfma_f32_32x32x2_f32: fp32 products, fp32 sums).  256 threads as
+// 2 x 2 waves, each wave a (TM/2) x (TN/2) part of the tile in 32 x 32 accumulator blocks.  One instruction takes
+// A[32 rows][2 k] and B[2 k][32 columns], one value per lane: lane l supplies row (column) l % 32 of reduction index
+// l / 32, and holds of the 32 x 32 result the entries (row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32), r < 16.
+// The fill fetches a whole reduction step into registers before it writes any of it to LDS (all loads in flight at
+// once; the accumulators live in the other half of the register file, so there is room).  LDS row pitch TM + 1: a
+// k-contiguous fill writes 32 consecutive k of one row, all banks once; an operand read takes 32 consecutive floats.
+template <int TM, int TN, int TK, bool AK, bool BK, class FA, class FB, class FOut>
+__device__ __forceinline__ void tile_product_mfma(int64_t M, int64_t Nn, int64_t K, int64_t m0, int64_t n0,
+                                                  FA A, FB Bm, FOut out) {
+  typedef __attribute__((ext_vector_type(16))) float f32x16;
+  constexpr int WM = TM / 2, WN = TN / 2, NBM = WM / 32, NBN = WN / 32;
+  __shared__ float As[TK][TM + 1];
+  __shared__ float Bs[TK][TN + 1];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave >> 1, wc = wave & 1, l32 = lane & 31, lh = lane >> 5;
+  f32x16 acc[NBM][NBN];
+#pragma unroll
+  for (int u = 0; u < NBM; ++u)
+#pragma unroll
+    for (int v = 0; v < NBN; ++v)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[u][v][r] = 0.f;
+  for (int64_t k0 = 0; k0 < K; k0 += TK) {
+    {
+      constexpr int NA = TM * TK / 256, NB = TN * TK / 256;
+      float ra[NA], rb[NB];
+#pragma unroll
+      for (int r = 0; r < NA; ++r) {
+        const int e = tid + r * 256, kk = AK ? e % TK : e / TM, mm = AK ? e / TK : e % TM;
+        const int64_t m = m0 + mm, k = k0 + kk;
+        ra[r] = (m < M && k < K) ? A(m, k) : 0.f;
+      }
+#pragma unroll
+      for (int r = 0; r < NB; ++r) {
+        const int e = tid + r * 256, kk = BK ? e % TK : e / TN, nn = BK ? e / TK : e % TN;
+        const int64_t n = n0 + nn, k = k0 + kk;
+        rb[r] = (n < Nn && k < K) ? Bm(k, n) : 0.f;
+      }
+#pragma unroll
+      for (int r = 0; r < NA; ++r) {
+        const int e = tid + r * 256;
+        As[AK ? e % TK : e / TM][AK ? e / TK : e % TM] = ra[r];
+      }
+#pragma unroll
+      for (int r = 0; r < NB; ++r) {
+        const int e = tid + r * 256;
+        Bs[BK ? e % TK : e / TN][BK ? e / TK : e % TN] = rb[r];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < TK; kk += 2) {
+      float a[NBM], bb[NBN];
+#pragma unroll
+      for (int u = 0; u < NBM; ++u) a[u] = As[kk + lh][wr * WM + u * 32 + l32];
+#pragma unroll
+      for (int v = 0; v < NBN; ++v) bb[v] = Bs[kk + lh][wc * WN + v * 32 + l32];
+#pragma unroll
+      for (int u = 0; u < NBM; ++u)
+#pragma unroll
+        for (int v = 0; v < NBN; ++v) acc[u][v] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], bb[v], acc[u][v], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int u = 0; u < NBM; ++u)
+#pragma unroll
+    for (int v = 0; v < NBN; ++v)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t m = m0 + wr * WM + u * 32 + (r >> 2) * 8 + lh * 4 + (r & 3), n = n0 + wc * WN + v * 32 + l32;
+        if (m < M && n < Nn) out(m, n, acc[u][v][r]);
+      }
+}
+
+// Which product runs where (measured at B = 32768, d = 512, b = 4096; ms for the two logit blocks):
+//  * fp32 features: the matrix-core product everywhere (similarities 2.6 against 4.0 on the vector ALUs, key side 2.6
+//    against 4.4, query side 3.2 against 4.6);
+//  * bf16 features (the widths the MFMA path does not take): their 2-byte loads make the batched fill slow, and the
+//    vector-ALU product with its element-by-element fill wins for the similarities (3.5 against 5.0) and the key
+//    side (4.3 against 5.2); the query side, whose left operand is the fp32 matrix in the workspace, stays on the
+//    matrix cores (5.0 against 5.4).
+// Output tiles: 128 x 128 where the grid is large (b x B similarities, B x d key-side gradient), 64 x 64 for the
+// b x d query-side gradient, whose grid would not fill the chip otherwise.
 constexpr int TS = 128;
 constexpr int TQ = 64;
+
+// AKV: the left operand's fill order on the vector-ALU variant (the key side runs 8 % faster there with consecutive
+// threads along the reduction index although its left operand is contiguous along m)
+template <int DT, int TM, int TN, bool AK, bool BK, bool AKV, class FA, class FB, class FOut>
+__device__ __forceinline__ void tile_product(int64_t M, int64_t Nn, int64_t K, int64_t m0, int64_t n0, FA A, FB Bm, FOut out) {
+  if constexpr (DT == DISCO_F32) tile_product_mfma<TM, TN, 16, AK, BK>(M, Nn, K, m0, n0, A, Bm, out);
+  else tile_product_valu<TM, TN, 16, AKV, BK>(M, Nn, K, m0, n0, A, Bm, out);
+}
 
 struct BlockView {
   const void* X;   // b x d local rows (already offset to the rank's first row)
@@ -127,13 +186,14 @@ __device__ __forceinline__ BlockView block_view(const void* I, const void* T, in
 }
 
 // Step 1 (Alg. 1 "scaled dot product similarities", without the multiplier): W[i][j] = <X_i, Y_j>.
+template <int DT>
 __global__ __launch_bounds__(256) void naive_similarity(const void* I, const void* T, int dtype, int64_t b,
                                                          int64_t B, int64_t d, int rank, float* ws) {
   BlockView v = block_view(I, T, dtype, b, B, d, rank, ws, blockIdx.z);
   int64_t m0 = (int64_t)blockIdx.y * TS, n0 = (int64_t)blockIdx.x * TS;
-  tile_product<TS, TS, 16, true, true, false>(
-      b, B, d, m0, n0, [&](int64_t m, int64_t k) { return load_feat(v.X, dtype, m * d + k); },
-      [&](int64_t k, int64_t n) { return load_feat(v.Y, dtype, n * d + k); },
+  tile_product<DT, TS, TS, true, true, true>(
+      b, B, d, m0, n0, [&](int64_t m, int64_t k) { return load_feat<DT>(v.X, m * d + k); },
+      [&](int64_t k, int64_t n) { return load_feat<DT>(v.Y, n * d + k); },
       [&](int64_t m, int64_t n, float a) { v.W[m * B + n] = a; });
 }
 
@@ -212,6 +272,7 @@ __global__ __launch_bounds__(256) void naive_scalars(const float* row_ce, const 
 // Step 4, key side (inter-rank term of Eq. 5 plus the key-side intra term): for every global row j
 //   gT[j] (+)= c s sum_i G^A[i][j] I_r[i]      (z = 0)
 //   gI[j] (+)= c s sum_i G^C[i][j] T_r[i]      (z = 1)
+template <int DT>
 __global__ __launch_bounds__(256) void naive_key_grad(const void* I, const void* T, int dtype, int64_t b, int64_t B,
                                                        int64_t d, int rank, float* ws, float cs, int accumulate,
                                                        float* gI, float* gT) {
@@ -220,9 +281,9 @@ __global__ __launch_bounds__(256) void naive_key_grad(const void* I, const void*
   float* out = z == 0 ? gT : gI;
   // the B key rows run along grid.x (up to 2^31 - 1 workgroups), the feature columns along grid.y
   int64_t m0 = (int64_t)blockIdx.x * TS, n0 = (int64_t)blockIdx.y * TS;
-  tile_product<TS, TS, 16, true, false, false>(
+  tile_product<DT, TS, TS, false, false, true>(
       B, d, b, m0, n0, [&](int64_t m, int64_t k) { return v.W[k * B + m]; },
-      [&](int64_t k, int64_t n) { return load_feat(v.X, dtype, k * d + n); },
+      [&](int64_t k, int64_t n) { return load_feat<DT>(v.X, k * d + n); },
       [&](int64_t m, int64_t n, float a) {
         float prev = accumulate ? out[m * d + n] : 0.f;
         out[m * d + n] = prev + cs * a;
@@ -233,6 +294,7 @@ __global__ __launch_bounds__(256) void naive_key_grad(const void* I, const void*
 //   gI[R_r][i] += c s sum_j G^A[i][j] T[j]     (z = 0)
 //   gT[R_r][i] += c s sum_j G^C[i][j] I[j]     (z = 1)
 // Runs after naive_key_grad on the same stream, so the rows already hold the key-side part.
+template <int DT>
 __global__ __launch_bounds__(256) void naive_query_grad(const void* I, const void* T, int dtype, int64_t b,
                                                          int64_t B, int64_t d, int rank, float* ws, float cs,
                                                          float* gI, float* gT) {
@@ -240,9 +302,9 @@ __global__ __launch_bounds__(256) void naive_query_grad(const void* I, const voi
   BlockView v = block_view(I, T, dtype, b, B, d, rank, ws, z);
   float* out = (z == 0 ? gI : gT) + (size_t)rank * b * d;
   int64_t m0 = (int64_t)blockIdx.y * TQ, n0 = (int64_t)blockIdx.x * TQ;
-  tile_product<TQ, TQ, 16, true, false, true>(
+  tile_product_mfma<TQ, TQ, 32, true, false>(
       b, d, B, m0, n0, [&](int64_t m, int64_t k) { return v.W[m * B + k]; },
-      [&](int64_t k, int64_t n) { return load_feat(v.Y, dtype, k * d + n); },
+      [&](int64_t k, int64_t n) { return load_feat<DT>(v.Y, k * d + n); },
       [&](int64_t m, int64_t n, float a) { out[m * d + n] += cs * a; });
 }
 
@@ -268,17 +330,22 @@ int naive_run(const Problem& p) {
   const float cs = c * p.s;
 
   stage_mark(p.stream, 0);
-  naive_similarity<<<dim3(cdiv(B, TS), cdiv(b, TS), nb), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W);
+  const bool bf = p.dtype == DISCO_BF16;
+  const dim3 sim_grid(cdiv(B, TS), cdiv(b, TS), nb);
+  if (bf) naive_similarity<DISCO_BF16><<<sim_grid, 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W);
+  else naive_similarity<DISCO_F32><<<sim_grid, 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W);
   stage_mark(p.stream, 1);
   naive_row_softmax<<<dim3((unsigned)b, nb), 256, 0, p.stream>>>(W, b, B, p.rank, p.s, row_ce, row_ds, p.variant);
   stage_mark(p.stream, 2);
   naive_scalars<<<1, 256, 0, p.stream>>>(row_ce, row_ds, (int64_t)nb * b, c, p.accumulate, p.loss, p.gs);
   stage_mark(p.stream, 3);
-  naive_key_grad<<<dim3(cdiv(B, TS), cdiv(d, TS), nb), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,
-                                                                          p.accumulate, p.gI, p.gT);
+  const dim3 key_grid(cdiv(B, TS), cdiv(d, TS), nb);
+  if (bf) naive_key_grad<DISCO_BF16><<<key_grid, 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs, p.accumulate, p.gI, p.gT);
+  else naive_key_grad<DISCO_F32><<<key_grid, 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs, p.accumulate, p.gI, p.gT);
   stage_mark(p.stream, 4);
-  naive_query_grad<<<dim3(cdiv(d, TQ), cdiv(b, TQ), nb), 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs,
-                                                                            p.gI, p.gT);
+  const dim3 query_grid(cdiv(d, TQ), cdiv(b, TQ), nb);
+  if (bf) naive_query_grad<DISCO_BF16><<<query_grid, 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs, p.gI, p.gT);
+  else naive_query_grad<DISCO_F32><<<query_grid, 256, 0, p.stream>>>(p.I, p.T, p.dtype, b, B, d, p.rank, W, cs, p.gI, p.gT);
   stage_mark(p.stream, 5);
   return hipGetLastError() == hipSuccess ? DISCO_OK : DISCO_ERR_HIP;
 }
