@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--config", default="b32k_n8")
     ap.add_argument("--path", default="auto", choices=["auto", "naive", "materialized", "fused", "symmetric"])
     ap.add_argument("--ranks", default="all", help="'all' (every simulated rank per step) or one rank index")
+    ap.add_argument("--features", default="config", choices=["config", "f32"],
+                    help="'f32': hand the workload's features over in fp32 whatever its dtype (they then take the fp32 path)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="capture one step (all rank calls) in a graph and time its replays")
     ap.add_argument("--op", default="loss", choices=["loss", "prep", "mfma-peak"],
@@ -122,7 +124,8 @@ def main():
             "fused": dl.DISCO_PATH_FUSED, "symmetric": dl.DISCO_PATH_SYMMETRIC}[args.path]
     I, T, Ib, Tb = make_config_inputs(cfg)
     dev = torch.device("cuda:0")
-    if cfg.dtype == "bf16":
+    feat_dtype = "f32" if args.features == "f32" else cfg.dtype
+    if feat_dtype == "bf16":
         Id = torch.from_numpy(Ib.view(np.int16)).to(dev)
         Td = torch.from_numpy(Tb.view(np.int16)).to(dev)
         dt = dl.DISCO_BF16
@@ -236,7 +239,7 @@ def main():
         dom_flops = 4.0 * b * B * d
         # fp32 features run on the fp32 matrix instruction, bf16 features partly on the vector ALUs: the published
         # peak is the same number for both
-        peak, bound, unit = PEAK_FP32_TFLOPS, ("mfma" if cfg.dtype != "bf16" else "alu"), "TFLOP/s"
+        peak, bound, unit = PEAK_FP32_TFLOPS, ("mfma" if feat_dtype != "bf16" else "alu"), "TFLOP/s"
         dtype = "f32"
     dom_ms = float(stage_avg[dom])
     achieved = dom_flops / (dom_ms * 1e-3) / 1e12
@@ -275,7 +278,7 @@ def main():
         "vs_baseline": (round(value / PAPER_SAMPLES_PER_S[cfg.name], 2) if cfg.name in PAPER_SAMPLES_PER_S else None),
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "B": B, "d": d, "N_simulated_ranks": N, "b": b, "s": round(s, 6),
-                   "ranks_per_step": calls_per_step, "path": PATH_NAMES[resolved],
+                   "features": feat_dtype, "ranks_per_step": calls_per_step, "path": PATH_NAMES[resolved],
                    "launch": "graph replay" if args.graph else "eager",
                    "workspace_bytes": ws_bytes},
         "ms_per_step_median": round(step_ms[len(step_ms) // 2], 4), "ms_per_step_min": round(step_ms[0], 4),
