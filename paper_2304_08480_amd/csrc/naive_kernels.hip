@@ -211,6 +211,30 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* red) 
   return r;
 }
 
+// One pass of a workgroup over a row of B floats: x <- f(j, x) for every column j (stored back if WRITE).  The row
+// starts at any float offset of a 256-byte aligned buffer: `head` (0..3) columns up to the first 16-byte boundary,
+// then 16-byte pieces, then up to 3 columns; the at most six odd columns go one per thread.
+template <bool WRITE, class F>
+__device__ __forceinline__ void row_visit(float* w, int64_t B, int head, F f) {
+  typedef __attribute__((ext_vector_type(4))) float f32x4;
+  const int64_t nvec = (B - head) >> 2;
+  for (int64_t q = threadIdx.x; q < nvec; q += 256) {
+    f32x4* p = reinterpret_cast<f32x4*>(w + head) + q;
+    f32x4 v = *p;
+    const int64_t j = head + q * 4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = f(j + e, v[e]);
+    if (WRITE) *p = v;
+  }
+  const int64_t t0 = head + nvec * 4;
+  const int nrest = head + (int)(B - t0);
+  if ((int)threadIdx.x < nrest) {
+    const int64_t j = (int)threadIdx.x < head ? (int64_t)threadIdx.x : t0 + ((int)threadIdx.x - head);
+    const float x = f(j, w[j]);
+    if (WRITE) w[j] = x;
+  }
+}
+
 // Step 2 (Alg. 1 cross_entropy_loss, and the softmax gradient of loss.backward()).  One workgroup per
 // local row: lse_i = m + log(sum exp(z - m)) over z = s * W[i][:], ce_i = lse_i - z[label], then
 // W[i][j] <- P_ij - [j = label].  The off-label mass is summed on its own so that P_label - 1 is
@@ -223,28 +247,34 @@ __global__ __launch_bounds__(256) void naive_row_softmax(float* ws, int64_t b, i
   __shared__ float red[4];
   const int z = blockIdx.y;
   const int64_t i = blockIdx.x;
-  float* w = ws + ((size_t)z * b + i) * B;
+  const int64_t row0 = ((int64_t)z * b + i) * B;
+  float* w = ws + row0;
+  const int64_t to_boundary = (4 - (row0 & 3)) & 3;
+  const int head = (int)(to_boundary < B ? to_boundary : B);
   const int64_t label = label_row((int64_t)rank * b + i, B, variant);
   const int64_t self = masked_col((int64_t)rank * b + i, variant);
   float mx = -INFINITY;
-  for (int64_t j = threadIdx.x; j < B; j += 256)
-    if (j != self) mx = fmaxf(mx, s * w[j]);
+  row_visit<false>(w, B, head, [&](int64_t j, float x) {
+    if (j != self) mx = fmaxf(mx, s * x);
+    return x;
+  });
   mx = block_reduce(mx, true, red);
   float off = 0.f;
-  for (int64_t j = threadIdx.x; j < B; j += 256)
-    if (j != label && j != self) off += expf(s * w[j] - mx);
+  row_visit<false>(w, B, head, [&](int64_t j, float x) {
+    if (j != label && j != self) off += expf(s * x - mx);
+    return x;
+  });
   off = block_reduce(off, false, red);
   const float zl = s * w[label];
   const float el = expf(zl - mx);
   const float tot = off + el;
   const float inv = 1.f / tot;
   float ds = 0.f;
-  for (int64_t j = threadIdx.x; j < B; j += 256) {
-    float cs = w[j];
-    float g = (j == label) ? -off * inv : (j == self) ? 0.f : expf(s * cs - mx) * inv;
-    ds = fmaf(g, cs, ds);
-    w[j] = g;
-  }
+  row_visit<true>(w, B, head, [&](int64_t j, float x) {
+    const float g = (j == label) ? -off * inv : (j == self) ? 0.f : expf(s * x - mx) * inv;
+    ds = fmaf(g, x, ds);
+    return g;
+  });
   ds = block_reduce(ds, false, red);
   if (threadIdx.x == 0) {
     // ce = log(tot) - (zl - mx).  When the label holds most of the mass this is log1p(off/el), which
