@@ -175,10 +175,16 @@ __global__ __launch_bounds__(256) void k_prep(Blocks bl, const uint16_t* I, cons
   const uint16_t* x = p.X + i * d;
   const uint16_t* y = p.Y + label_row((int64_t)rank * b + i, B, bl.variant) * d;
   float dot = 0.f, nn = 0.f;
-  for (int64_t k = lane; k < d; k += 64) {
-    float xv = __uint_as_float((uint32_t)x[k] << 16), yv = __uint_as_float((uint32_t)y[k] << 16);
-    dot = fmaf(xv, yv, dot);
-    nn = fmaf(xv, xv, nn);
+  for (int64_t k = lane * 8; k < d; k += 512) {          // 16-byte pieces (d is a multiple of 8, the rows are 16-byte aligned)
+    const u32x4 xw = *reinterpret_cast<const u32x4*>(x + k), yw = *reinterpret_cast<const u32x4*>(y + k);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float x0 = bf16_lo(xw[q]), x1 = bf16_hi(xw[q]);
+      dot = fmaf(x0, bf16_lo(yw[q]), dot);
+      dot = fmaf(x1, bf16_hi(yw[q]), dot);
+      nn = fmaf(x0, x0, nn);
+      nn = fmaf(x1, x1, nn);
+    }
   }
   dot = wave_sum(dot);
   nn = wave_sum(nn);
