@@ -178,3 +178,14 @@ def test_auto_sends_ragged_shares_to_the_tile_kernels_when_large_enough():
     assert dl.disco_resolve_path(1000, 256, 1, dt, dl.DISCO_PATH_SYMMETRIC) == dl.DISCO_PATH_SYMMETRIC
     assert dl.disco_resolve_path(1000, 256, 2, dt, dl.DISCO_PATH_FUSED) == dl.DISCO_PATH_FUSED
     assert dl.disco_workspace_bytes(1000, 256, 2, dt, dl.DISCO_PATH_MATERIALIZED) > dl.disco_workspace_bytes(1024, 256, 2, dt, dl.DISCO_PATH_MATERIALIZED)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Every box has one GPU: `bench.py --gpus N` with N above 1 exits with a message, before any GPU work."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
