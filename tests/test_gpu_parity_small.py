@@ -46,7 +46,9 @@ def test_tiny_every_rank_and_rank_sum():
 
 @pytest.mark.parametrize("B,d,N,s,dtype", [(300, 77, 3, 14.285714, "f32"), (130, 33, 1, 100.0, "f32"),
                                            (192, 65, 64, 5.0, "bf16"), (8, 4, 8, 20.0, "f32"),
-                                           (1, 16, 1, 3.0, "f32")])
+                                           (1, 16, 1, 3.0, "f32"),
+                                           # several tiles with ragged tails in every dimension of all three products
+                                           (1000, 200, 2, 14.285714, "f32"), (1040, 72, 2, 14.285714, "bf16")])
 def test_ragged_shapes_naive(B, d, N, s, dtype):
     I, T = clip_pairs(B, d, 7)
     Ib = Tb = None
