@@ -5,7 +5,8 @@ b32k_n8 (B=32768, d=512, N=8, bf16): two ranks dense against the per-rank oracle
 the non-decomposed entry point (full_n1, both bf16 paths) dense against the oracle of the original loss (Eq. 1).
 The larger workloads (B=196608 / N=64 at s=100, its weak-positive variant, B=65536 / d=768 / N=8 with
 near-duplicate rows, the paper's own shapes B=32768 and 65536 on 64 ranks, and a batch of 30000 on 8 ranks, whose
-3750-pair shares are not whole tiles): one rank dense against the per-rank oracle, d/ds included.  The float64 references of one workload are computed once per session.
+3750-pair shares are not whole tiles): one rank dense against the per-rank oracle, d/ds included.  b32k_n8 once more with
+its features handed over in fp32 (the fp32 path at the real shape).  The float64 references of one workload are computed once per session.
 """
 import functools
 import time
@@ -69,6 +70,27 @@ def test_b32k_n8_ranks_dense():
         ref = oc.disco_rank(I, T, cfg.s, r, cfg.N)
         sc = term_scale(oc, I, T, cfg.s, r, cfg.N)
         _check(f"b32k_n8 rank {r} [oracle {time.time() - t0:.1f}s]", run, ref, sc)
+
+
+def test_b32k_n8_fp32_features_rank_dense():
+    """The same workload handed over in fp32 (the features' exact upcasts): the fp32 path on the fp32 matrix instruction,
+    one rank at the real shape, every entry against the per-rank oracle at the fp32 bars."""
+    cfg, I, T, _, _ = _inputs("b32k_n8")
+    Id, Td, dt = to_device(I, T, None, None, "f32")
+    assert dl.disco_resolve_path(cfg.B, cfg.d, cfg.N, dt, dl.DISCO_PATH_AUTO) == dl.DISCO_PATH_NAIVE
+    run = Runner(Id, Td, cfg.B, cfg.d, cfg.N, dt, dl.DISCO_PATH_AUTO)
+    r = 3
+    print(f"case b32k_n8 fp32 features rank {r}", flush=True)
+    run.rank(r, cfg.s)
+    ref = oc.disco_rank(I, T, cfg.s, r, cfg.N)
+    sc = term_scale(oc, I, T, cfg.s, r, cfg.N)
+    loss, gI, gT, gs = run.results()
+    e1 = check_scalar("fp32 loss", loss, ref[0], TOL["f32"]["scalar"])
+    e2 = check_scalar("fp32 gs", gs, ref[3], TOL["f32"]["scalar"] * 10, abs_tol=1e-9)
+    f1 = check_tensor("fp32 gI", gI, ref[1], "f32", sc[0], sc[2])
+    f2 = check_tensor("fp32 gT", gT, ref[2], "f32", sc[1], sc[2])
+    print(f"b32k_n8 fp32 features rank {r}: loss err {e1:.2e} gs err {e2:.2e} gI (fro, bound ratio) ({f1[0]:.2e}, {f1[1]:.3f}) "
+          f"gT ({f2[0]:.2e}, {f2[1]:.3f})", flush=True)
 
 
 def test_b32k_n8_accumulated_against_the_full_loss():
