@@ -696,6 +696,21 @@ __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b
   store_tile_f32<ACCUMULATE>(acc, smem, p.part + (int64_t)ks * b * d + i0 * d + k0, d, 1.0f, ncols);
 }
 
+// Sum over the split-K slices ks0, ks0 + step, ... (< splitk), in that order, of the 16-byte piece of row i at feature
+// k of each slice (part[(ks * pitch + i) * d + k]); four loads in flight at a time (a plain loop waits for every load).
+__device__ __forceinline__ f32x4 sum_slices(const float* part, int64_t pitch, int64_t i, int64_t d, int64_t k, int ks0, int step,
+                                            int splitk) {
+  auto piece = [&](int ks) { return *reinterpret_cast<const f32x4*>(part + ((int64_t)ks * pitch + i) * d + k); };
+  f32x4 u = {0.f, 0.f, 0.f, 0.f};
+  int ks = ks0;
+  for (; ks + 3 * step < splitk; ks += 4 * step) {
+    const f32x4 v0 = piece(ks), v1 = piece(ks + step), v2 = piece(ks + 2 * step), v3 = piece(ks + 3 * step);
+    u += v0; u += v1; u += v2; u += v3;
+  }
+  for (; ks < splitk; ks += step) u += piece(ks);
+  return u;
+}
+
 // Everything that lands in the rank's own rows, for both blocks at once.  With lab = label of local row i:
 //   gI[lab] += cs (beta^A_i sum_ks part^A + gdiag^A_i T[lab])    query side of block A (Eq. 4)
 //            + cs gdiag^C_i T[lab]                                label-column term of block C's key side
@@ -707,7 +722,6 @@ __global__ __launch_bounds__(NTHREADS) void k_query_partial(Blocks bl, int64_t b
 template <bool ROWWG>
 __global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int64_t b, int64_t bp, int64_t d, int rank, float cs, int splitk) {
   if (gated_off(bl)) return;
-  typedef __attribute__((ext_vector_type(4))) float f32x4;
   __shared__ f32x4 others[ROWWG ? 3 : 1][2][64];
   const BlockPtrs& pa = bl.z[0];
   const BlockPtrs& pc = bl.z[1];
@@ -721,11 +735,10 @@ __global__ __launch_bounds__(256) void k_query_finalize(Blocks bl, int64_t b, in
     const int64_t k = kc + lane * 4;
     const bool on = k < d;
     f32x4 ua = {0.f, 0.f, 0.f, 0.f}, uc = {0.f, 0.f, 0.f, 0.f};
-    if (on)
-      for (int ks = ROWWG ? wave : 0; ks < splitk; ks += ROWWG ? 4 : 1) {
-        ua += *reinterpret_cast<const f32x4*>(pa.part + ((int64_t)ks * bp + i) * d + k);
-        uc += *reinterpret_cast<const f32x4*>(pc.part + ((int64_t)ks * bp + i) * d + k);
-      }
+    if (on) {
+      ua = sum_slices(pa.part, bp, i, d, k, ROWWG ? wave : 0, ROWWG ? 4 : 1, splitk);
+      uc = sum_slices(pc.part, bp, i, d, k, ROWWG ? wave : 0, ROWWG ? 4 : 1, splitk);
+    }
     if (ROWWG) {
       if (wave > 0) { others[wave - 1][0][lane] = ua; others[wave - 1][1][lane] = uc; }
       __syncthreads();
@@ -773,7 +786,6 @@ constexpr int64_t FINALIZE_ROWWG_MAX = 1024;
 // b: the real rows; bp: row pitch of the partial products.
 __global__ __launch_bounds__(256) void k_query_finalize_ntxent(Blocks bl, int64_t b, int64_t bp, int64_t B, int64_t d, int rank, float cs, int splitk) {
   if (gated_off(bl)) return;
-  typedef __attribute__((ext_vector_type(4))) float f32x4;
   const BlockPtrs& p = bl.z[0];
   const int lane = threadIdx.x & 63;
   const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -785,8 +797,7 @@ __global__ __launch_bounds__(256) void k_query_finalize_ntxent(Blocks bl, int64_
   const uint16_t* Zfull = p.Y;
   float dot = 0.f;
   for (int64_t k = lane * 4; k < d; k += 256) {
-    f32x4 u = {0.f, 0.f, 0.f, 0.f};
-    for (int ks = 0; ks < splitk; ++ks) u += *reinterpret_cast<const f32x4*>(p.part + ((int64_t)ks * bp + i) * d + k);
+    const f32x4 u = sum_slices(p.part, bp, i, d, k, 0, 1, splitk);
     const u32x2 zw = *reinterpret_cast<const u32x2*>(Zfull + g * d + k);        // Z[g]
     const u32x2 pw = *reinterpret_cast<const u32x2*>(Zfull + lab * d + k);      // Z[lab]
     const float zv[4] = {bf16_lo(zw[0]), bf16_hi(zw[0]), bf16_lo(zw[1]), bf16_hi(zw[1])};
@@ -814,7 +825,17 @@ __global__ __launch_bounds__(1024) void k_scalars(Blocks bl, int64_t b, float c,
   __shared__ float ra[16], rg[16];
   float a = 0.f, g = 0.f;
   for (int z = 0; z < bl.nblk; ++z)
-    for (int64_t i = threadIdx.x; i < b; i += 1024) { a += bl.z[z].ce[i]; g += bl.z[z].rowds[i]; }
+    for (int64_t i0 = threadIdx.x; i0 < b; i0 += 4096) {              // four loads of each array in flight
+      float c[4], r[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int64_t i = i0 + u * 1024;
+        c[u] = i < b ? bl.z[z].ce[i] : 0.f;
+        r[u] = i < b ? bl.z[z].rowds[i] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { a += c[u]; g += r[u]; }
+    }
   a = wave_sum(a);
   g = wave_sum(g);
   if ((threadIdx.x & 63) == 0) { ra[threadIdx.x >> 6] = a; rg[threadIdx.x >> 6] = g; }
@@ -981,8 +1002,7 @@ __global__ __launch_bounds__(256) void k_sym_finalize(Blocks bl, int64_t B, int6
   const float gd = p.gdiag[i] + bl.z[1].gdiag[i];
   float dot = 0.f;
   for (int64_t k = lane * 4; k < d; k += 256) {
-    f32x4 u = {0.f, 0.f, 0.f, 0.f};
-    for (int ks = 0; ks < splitk; ++ks) u += *reinterpret_cast<const f32x4*>(p.part + ((int64_t)ks * Bp + i) * d + k);
+    const f32x4 u = sum_slices(p.part, Bp, i, d, k, 0, 1, splitk);
     const u32x2 iw = *reinterpret_cast<const u32x2*>(p.X + i * d + k);
     const u32x2 tw = *reinterpret_cast<const u32x2*>(p.Y + i * d + k);
     const float iv[4] = {bf16_lo(iw[0]), bf16_hi(iw[0]), bf16_lo(iw[1]), bf16_hi(iw[1])};
