@@ -434,30 +434,48 @@ __device__ __forceinline__ float row_outputs(const BlockPtrs& p, int64_t i, floa
 }
 
 // Xs[k][i] = bf16(scale_i x_ik) for the nrows (a multiple of 64) rows from i0 on, scale = the nrows floats at `scale`
-// in LDS (nullptr: 1): the key-side contraction's right operand, with its reduction index contiguous.  All threads of
-// the workgroup (a multiple of 256, at most 1024), 64 x 64 pieces through `tile` (64 x 65 floats of LDS).
+// in LDS (nullptr: 1): the key-side contraction's right operand, with its reduction index contiguous.  All NTH threads
+// of the workgroup (512 or 1024), 64 x 64 pieces through `tile` (64 x 65 floats of LDS).  The pieces of up to eight
+// 64-feature tiles are fetched before the first is turned round, so that their loads are in flight together.
+template <int NTH>
 __device__ __forceinline__ void scale_transpose_rows(const BlockPtrs& p, int64_t b, int64_t d, int64_t i0, int nrows, const float* scale,
                                                      float (*tile)[65]) {
-  const int t = threadIdx.x, nth = blockDim.x;
+  constexpr int NPT = 1024 / NTH, AHEAD = 8;              // pieces of 4 features per thread and tile; tiles per batch
+  const int t = threadIdx.x;
   for (int r0 = 0; r0 < nrows; r0 += 64)
-    for (int64_t k0 = 0; k0 < d; k0 += 64) {
-      __syncthreads();                                    // the tile's previous contents have been read
-      for (int e = t; e < 1024; e += nth) {               // 64 rows x 16 pieces of 4 features
-        const int r = e >> 4, c4 = (e & 15) * 4;
-        const u32x2 w = *reinterpret_cast<const u32x2*>(p.X + (i0 + r0 + r) * d + k0 + c4);
-        const float sc = scale ? scale[r0 + r] : 1.f;
-        tile[r][c4 + 0] = sc * bf16_lo(w[0]);
-        tile[r][c4 + 1] = sc * bf16_hi(w[0]);
-        tile[r][c4 + 2] = sc * bf16_lo(w[1]);
-        tile[r][c4 + 3] = sc * bf16_hi(w[1]);
-      }
-      __syncthreads();
-      for (int e = t; e < 1024; e += nth) {               // 64 features x 16 pieces of 4 rows
-        const int k = e >> 4, i4 = (e & 15) * 4;
-        bf16x4 v;
+    for (int64_t kc = 0; kc < d; kc += 64 * AHEAD) {
+      u32x2 w[AHEAD][NPT];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = (__bf16)tile[i4 + j][k];
-        *reinterpret_cast<bf16x4*>(p.Xs + (k0 + k) * b + i0 + r0 + i4) = v;
+      for (int a = 0; a < AHEAD; ++a)
+        if (kc + a * 64 < d)
+#pragma unroll
+          for (int q = 0; q < NPT; ++q) {                 // 64 rows x 16 pieces of 4 features
+            const int e = t + q * NTH, r = e >> 4, c4 = (e & 15) * 4;
+            w[a][q] = *reinterpret_cast<const u32x2*>(p.X + (i0 + r0 + r) * d + kc + a * 64 + c4);
+          }
+#pragma unroll
+      for (int a = 0; a < AHEAD; ++a) {
+        const int64_t k0 = kc + a * 64;
+        if (k0 >= d) break;
+        __syncthreads();                                  // the tile's previous contents have been read
+#pragma unroll
+        for (int q = 0; q < NPT; ++q) {
+          const int e = t + q * NTH, r = e >> 4, c4 = (e & 15) * 4;
+          const float sc = scale ? scale[r0 + r] : 1.f;
+          tile[r][c4 + 0] = sc * bf16_lo(w[a][q][0]);
+          tile[r][c4 + 1] = sc * bf16_hi(w[a][q][0]);
+          tile[r][c4 + 2] = sc * bf16_lo(w[a][q][1]);
+          tile[r][c4 + 3] = sc * bf16_hi(w[a][q][1]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < NPT; ++q) {                   // 64 features x 16 pieces of 4 rows
+          const int e = t + q * NTH, k = e >> 4, i4 = (e & 15) * 4;
+          bf16x4 v;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = (__bf16)tile[i4 + j][k];
+          *reinterpret_cast<bf16x4*>(p.Xs + (k0 + k) * b + i0 + r0 + i4) = v;
+        }
       }
     }
 }
@@ -521,7 +539,7 @@ __global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int np
       }
     }
   }
-  if (d > 0 && (int64_t)blockIdx.x * 64 + 64 <= b) scale_transpose_rows(p, b, d, (int64_t)blockIdx.x * 64, 64, beta_s, tile);
+  if (d > 0 && (int64_t)blockIdx.x * 64 + 64 <= b) scale_transpose_rows<1024>(p, b, d, (int64_t)blockIdx.x * 64, 64, beta_s, tile);
 }
 
 // The statistics kernels of a flagged query tile, redone by one workgroup per (block, query tile): a first
@@ -622,7 +640,7 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
     }
   }
   // the rows' share of Xs = (beta x)^T, written by k_row_merge with the betas that have just been replaced
-  scale_transpose_rows(p, b, d, i0, BN, red + 1024, reinterpret_cast<float (*)[65]>(red + 1280));
+  scale_transpose_rows<NTHREADS>(p, b, d, i0, BN, red + 1024, reinterpret_cast<float (*)[65]>(red + 1280));
 }
 
 // Xs = X^T for one block without any scaling (the symmetric full loss folds both normalisations into the stored
@@ -630,7 +648,7 @@ __global__ __launch_bounds__(NTHREADS) void k_logit_repair(Blocks bl, int64_t b,
 __global__ __launch_bounds__(1024) void k_transpose(Blocks bl, int64_t b, int64_t d) {
   if (gated_off(bl)) return;
   __shared__ float tile[64][65];
-  scale_transpose_rows(bl.z[0], b, d, (int64_t)blockIdx.x * 64, 64, nullptr, tile);
+  scale_transpose_rows<1024>(bl.z[0], b, d, (int64_t)blockIdx.x * 64, 64, nullptr, tile);
 }
 
 // Key-side gradient without its label-column term: gk[j][k] (+)= cs * sum_i E[i][j] Xs[k][i].
