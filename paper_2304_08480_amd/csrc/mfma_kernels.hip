@@ -506,6 +506,13 @@ __global__ __launch_bounds__(1024) void k_row_merge(Blocks bl, int64_t b, int np
   float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
   if (i < b) {
     int q = wave;
+    for (; q + 112 < nparts; q += 128) {                 // eight loads in flight
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = p.lpart[(int64_t)(q + 16 * u) * b + i];
+      a0 += v[0]; a1 += v[1]; a2 += v[2]; a3 += v[3];
+      a0 += v[4]; a1 += v[5]; a2 += v[6]; a3 += v[7];
+    }
     for (; q + 48 < nparts; q += 64) {
       a0 += p.lpart[(int64_t)q * b + i];
       a1 += p.lpart[(int64_t)(q + 16) * b + i];
