@@ -33,3 +33,10 @@ def test_bench_line_has_the_contract_fields():
     assert roof["traffic"] is not None and roof["traffic"] > 5e8
     cpu = out["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1 and "rank call" in cpu["sample"]
+
+
+def test_smoke_entry_runs():
+    """`__graft_entry__.smoke()`: one small call per path on cuda:0, checked against the oracle inside."""
+    sys.path.insert(0, ROOT)
+    import __graft_entry__ as entry
+    entry.smoke()
